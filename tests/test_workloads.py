@@ -1,0 +1,47 @@
+"""The seeded generators: determinism, shapes, dtype rounding, spike structure."""
+import numpy as np
+import torch
+
+from workloads import CONFIGS, make_custom, make_workload, round_to_bf16, bf16_bits
+
+
+def test_bf16_rounding_matches_torch_round_to_nearest_even():
+    r = np.random.Generator(np.random.PCG64(0))
+    x = np.concatenate([r.standard_normal(4096).astype(np.float32) * 10,
+                        np.array([1.00390625, 1.01171875, 0.0, -0.0, 3.0e38, 1e-40], dtype=np.float32)])
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    got = round_to_bf16(x)
+    assert got.tobytes() == ref.tobytes()
+    assert np.all((got.view(np.uint32) & 0xFFFF) == 0)
+    back = (bf16_bits(got).astype(np.uint32) << 16).view(np.float32)
+    assert back.tobytes() == got.tobytes()
+
+
+def test_same_seed_same_tensors_and_shapes():
+    a, b = make_workload(1), make_workload(1)
+    s = CONFIGS[1]
+    assert a.Q.shape == (s.B, s.Hq, s.n, s.d) and a.K.shape == (s.B, s.Hkv, s.n, s.d)
+    assert a.Q.tobytes() == b.Q.tobytes() and a.K.tobytes() == b.K.tobytes() and a.V.tobytes() == b.V.tobytes()
+    assert a.probe_pos.tolist() == list(range(576 - 64, 576))
+    assert make_workload(1, seed=5).K.tobytes() != a.K.tobytes()
+    assert len(a.spikes) == 4 and all(len(x) == 58 for x in a.spikes)
+
+
+def test_spiked_keys_stand_out_along_the_mean_query_direction():
+    w = make_custom(1, 2, 1, 256, 32, "bf16", seed=1, spike=3.0, spike_frac=0.1)
+    qbar = w.Q[0].mean(axis=(0, 1))
+    proj = w.K[0, 0] @ (qbar / np.linalg.norm(qbar))
+    S = w.spikes[0]
+    rest = np.setdiff1d(np.arange(256), S)
+    assert proj[S].mean() - proj[rest].mean() > 2.0
+    assert np.all((w.K.view(np.uint32) & 0xFFFF) == 0)      # bf16-representable
+
+
+def test_gqa_long_video_spikes_sit_in_four_frame_runs():
+    spec = CONFIGS[4]
+    assert spec.n == 128 * 144 and spec.Hq == 28 and spec.Hkv == 4
+    # only the spike-set logic is exercised here (full tensors are large)
+    from workloads.generators import _spike_set
+    r = np.random.Generator(np.random.PCG64(3))
+    S = _spike_set(4, spec, r, 0)
+    assert len(S) == 553 and len(np.unique(S // (8 * 144))) <= 4
