@@ -1,0 +1,164 @@
+/*
+ * zipvl.h - C ABI of the MI355X (gfx950) ZipVL prefill library.
+ *
+ * The calls follow the paper's statement of the method (arXiv 2410.08584):
+ * Algorithm 1 (prefill: probe scores -> adaptive count -> important set ->
+ * attention over the kept tokens -> KV-cache eviction) and Algorithm 2
+ * (decode against the evicted cache).
+ *
+ * General rules
+ *  - Every pointer marked [device] is GPU memory owned by the caller; the
+ *    library borrows it for the duration of the stream-ordered work and never
+ *    allocates, frees or synchronises.  Pointers marked [host] are read on the
+ *    host before the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - Tensors are addressed as base + b*stride[0] + h*stride[1] + t*stride[2]
+ *    + c, strides in ELEMENTS, last dimension (d) contiguous; every row start
+ *    must be 16-byte aligned.  Both [B,H,n,d] and [B,n,H,d] memory orders work.
+ *  - dtype 0 = IEEE fp32, 1 = bfloat16 (storage); all arithmetic accumulates
+ *    in fp32.  d must be 64 or 128.
+ *  - A "selection unit" is one (batch, KV head); unit index u = b*Hkv + g.
+ *    With grouped-query attention (Hq = G*Hkv) query head h belongs to KV head
+ *    h / G.
+ *  - Return value: ZIPVL_OK or a negative error code; the text of the last
+ *    error of the calling thread is returned by zipvl_last_error().  Invalid
+ *    arguments are rejected before any kernel is launched.
+ */
+#ifndef ZIPVL_H
+#define ZIPVL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZIPVL_OK             0
+#define ZIPVL_EINVAL        -1  /* NULL pointer, negative size, tau outside (0,1], bad probe list */
+#define ZIPVL_ESHAPE        -2  /* Hq % Hkv != 0, d not 64/128, n or m beyond the supported maximum */
+#define ZIPVL_EALIGN        -3  /* pointer or row stride not 16-byte aligned */
+#define ZIPVL_EWORKSPACE    -4  /* workspace missing or too small */
+#define ZIPVL_EUNSUPPORTED  -5  /* unknown dtype or flag */
+#define ZIPVL_EHIP          -6  /* kernel launch failed */
+
+#define ZIPVL_F32   0
+#define ZIPVL_BF16  1
+
+#define ZIPVL_MAX_PROBES 64
+
+/* ops for zipvl_workspace_bytes */
+#define ZIPVL_OP_SCORE          1
+#define ZIPVL_OP_SELECT         2
+#define ZIPVL_OP_SPARSE_PREFILL 3
+#define ZIPVL_OP_DECODE         4
+
+/* flags of zipvl_sparse_prefill */
+#define ZIPVL_OUT_FULL            0  /* O is [B,Hq,n,d]; rows of dropped tokens are written as zeros */
+#define ZIPVL_OUT_COMPACT         1  /* O row i of a head is kept token i (first k rows written) */
+#define ZIPVL_KV_ALREADY_COMPACT  2  /* K,V hold the evicted cache: row i is kept token i */
+
+typedef struct zipvl_dims {
+    int32_t B, Hq, Hkv, n, d;
+    int32_t dtype;            /* ZIPVL_F32 | ZIPVL_BF16 */
+    int64_t q_strides[3];     /* (batch, head, token) strides of Q in elements */
+    int64_t k_strides[3];
+    int64_t v_strides[3];
+} zipvl_dims;
+
+int zipvl_version(void);
+const char* zipvl_last_error(void);
+
+/* Bytes of [device] workspace the given op needs for these dims (m = number of
+ * probe rows for ZIPVL_OP_SCORE, ignored otherwise).  0 on invalid dims. */
+size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m);
+
+/*
+ * Token importance from a fixed, small set of probe queries.
+ * Paper: supplementary Section A, Eq. (A) (probe attention), Eq. (6)
+ * (accumulated score) and Eq. (8) (normalised score); Algorithm 1, steps 2-4.
+ *
+ *   A'[c,j] = softmax_j( Q[h,P_c] . K[g,j] * softmax_scale ),  keys j > P_c masked
+ *   a_j     = sum_c A'[c,j]
+ *   mass[u,j] = mean over the G heads of the group of  a_j / m
+ *   rank[u,j] = mean over the G heads of the group of  a_j / #{c : P_c >= j}   (0 if none)
+ *
+ * Q [device]          [B,Hq,n,d] by q_strides (only the probe rows are read)
+ * K [device]          [B,Hkv,n,d] by k_strides
+ * probe_pos [host]    m token positions, strictly ascending, 0 <= P_c < n, 1 <= m <= ZIPVL_MAX_PROBES
+ * mass, rank [device] [B*Hkv, n] fp32 contiguous, written for every j (rank may be NULL)
+ * ws [device]         zipvl_workspace_bytes(ZIPVL_OP_SCORE, dims, m) bytes, 16-byte aligned
+ * A' is never written to memory.  mass of a unit sums to 1 (up to fp32 rounding).
+ */
+int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims,
+                const int32_t* probe_pos, int m, float softmax_scale,
+                float* mass, float* rank, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * How many tokens to keep and which.  Paper: Eq. (7) (smallest count whose
+ * sorted accumulated scores reach tau of the total) and Eq. (9) (that many
+ * tokens with the largest normalised score); Algorithm 1, steps 3-5.
+ *
+ * Per unit u (row u of mass/rank, n entries each, finite and >= 0, sum < 4096):
+ *   q_j = floor(mass_j * 2^40)  (exact integers; the sums below are integer sums)
+ *   k   = n if tau >= 1, else max(1, min{ i : sum of the i largest q >= ceil(tau * sum of all q) })
+ *   T   = the k tokens with the largest rank (equal values: lower index first)
+ * idx[u, 0..k-1] receives T in ascending position; idx[u, k..n-1] is left as is.
+ *
+ * mass [device] [units,n] fp32; rank [device] same shape or NULL (use mass for both steps)
+ * tau in (0,1];  idx [device] [units,n] int32;  k [device] [units] int32
+ * ws may be NULL (no workspace is needed; the arguments exist for symmetry).
+ */
+int zipvl_select(const float* mass, const float* rank, int units, int n, double tau,
+                 int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Causal attention over the kept tokens only.  Paper: Section 4.2 and
+ * Algorithm 1, sparse-attention step (O = Attention(Q[T], K[T], V[T])), Eq. (2)
+ * restricted to T; outputs of dropped tokens are padded (with zeros here).
+ *
+ * For every query head h of unit u, with T = idx[u, 0..k[u]-1] (ascending):
+ *   O[h, T_i] = sum_{j<=i} softmax_j( Q[h,T_i] . K[g,T_j] * softmax_scale ) V[g,T_j]
+ * idx, k [device] as written by zipvl_select; both NULL = every token kept (dense).
+ * flags: ZIPVL_OUT_FULL (default) | ZIPVL_OUT_COMPACT | ZIPVL_KV_ALREADY_COMPACT.
+ * O [device] [B,Hq,n,d] contiguous, dtype as the inputs.
+ * ws [device] zipvl_workspace_bytes(ZIPVL_OP_SPARSE_PREFILL, dims, 0) bytes, 256-byte aligned.
+ */
+int zipvl_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims* dims,
+                         const int32_t* idx, const int32_t* k, float softmax_scale, int flags,
+                         void* O, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * KV-cache eviction.  Paper: Section 4.2, Algorithm 1 cache step (K <- K[T], V <- V[T]).
+ * Kc[u, i, :] = K[g, T_i, :], Vc likewise (bit copies), len[u] = k[u].
+ * Kc, Vc [device] [B*Hkv, cap, d] contiguous; cap >= max k (rows beyond cap are
+ * not written and len is clamped to cap).  idx,k NULL = copy all n rows.
+ */
+int zipvl_compact_kv(const void* K, const void* V, const zipvl_dims* dims,
+                     const int32_t* idx, const int32_t* k,
+                     void* Kc, void* Vc, int32_t cap, int32_t* len, void* stream);
+
+/*
+ * Decode step, cache side.  Paper: Eq. (4) / Algorithm 2 (K_out = Concat(K_in, k)).
+ * Writes k_new[u,:], v_new[u,:] ([B*Hkv, d] contiguous) at row len[u] of each
+ * unit's cache and increments len[u]; a full cache (len == cap) is left unchanged.
+ * dims->n is ignored; dims->dtype, B, Hkv, d are used.
+ */
+int zipvl_kv_append(void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
+                    const void* v_new, const zipvl_dims* dims, void* stream);
+
+/*
+ * Decode step, attention side.  Paper: Eq. (5) / Algorithm 2:
+ *   o[h] = softmax( q[h] . Kc[u, 0..len[u]-1]^T * softmax_scale ) Vc[u, 0..len[u]-1]
+ * q, o [device] [B*Hq, d] contiguous; Kc, Vc [device] [B*Hkv, cap, d]; len [device] [B*Hkv].
+ * Memory-bound: each cached row is read once per call.  G = Hq/Hkv <= 8.
+ * ws [device] zipvl_workspace_bytes(ZIPVL_OP_DECODE, dims (n = cap), 0) bytes.
+ */
+int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32_t* len,
+                      int32_t cap, const zipvl_dims* dims, float softmax_scale,
+                      void* o, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZIPVL_H */

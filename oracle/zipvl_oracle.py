@@ -233,3 +233,17 @@ def attention_flops_reduction(ratio: float) -> float:
 def kv_cache_reduction(ratio: float) -> float:
     """The cache is linear in the kept count (Section 4.2): 1 - r."""
     return 1.0 - ratio
+
+
+def kept_token_attention_rows(Qh, Kg, Vg, T, rows, scale) -> np.ndarray:
+    """Rows `rows` (indices into T) of kept_token_attention's compact output,
+    each taken directly from the definition: kept query T_i attends the kept
+    keys T_0..T_i.  For spot checks at sizes where the full product is slow."""
+    T = np.asarray(T, dtype=np.int64)
+    out = np.empty((len(rows), np.asarray(Vg).shape[1]))
+    for o, i in enumerate(rows):
+        keys = T[: i + 1]
+        s = (np.asarray(Kg, dtype=np.float64)[keys] @ np.asarray(Qh, dtype=np.float64)[T[i]]) * float(scale)
+        e = np.exp(s - s.max())
+        out[o] = (e / e.sum()) @ np.asarray(Vg, dtype=np.float64)[keys]
+    return out

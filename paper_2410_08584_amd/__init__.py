@@ -1,0 +1,17 @@
+"""MI355X-native ZipVL prefill path: thin Python binding over libzipvl.so (C ABI).
+
+Every step runs in the HIP kernels of the shared library; this package only
+marshals arguments (device pointers, strides, the current HIP stream).  There
+is no CPU fallback: calling any op without the built library raises.
+"""
+from .binding import (ZipvlError, library_path, load_library, dims_of, workspace_bytes,
+                      zipvl_score, zipvl_select, zipvl_sparse_prefill, zipvl_compact_kv,
+                      zipvl_kv_append, zipvl_decode_attn, zipvl_version, zipvl_last_error,
+                      OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT,
+                      OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, EXPORTS)
+
+__all__ = ["ZipvlError", "library_path", "load_library", "dims_of", "workspace_bytes",
+           "zipvl_score", "zipvl_select", "zipvl_sparse_prefill", "zipvl_compact_kv",
+           "zipvl_kv_append", "zipvl_decode_attn", "zipvl_version", "zipvl_last_error",
+           "OUT_FULL", "OUT_COMPACT", "KV_ALREADY_COMPACT",
+           "OP_SCORE", "OP_SELECT", "OP_SPARSE_PREFILL", "OP_DECODE", "EXPORTS"]

@@ -1,0 +1,222 @@
+"""ctypes binding of include/zipvl.h.  Tensors are torch CUDA(HIP) tensors used
+purely as device memory; the stream is torch's current stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libzipvl.so"
+
+OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT = 0, 1, 2
+OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE = 1, 2, 3, 4
+
+EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
+           "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn")
+
+
+class ZipvlError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"zipvl error {code}: {text}")
+        self.code = code
+
+
+class Dims(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("n", C.c_int32), ("d", C.c_int32),
+                ("dtype", C.c_int32), ("q_strides", C.c_int64 * 3), ("k_strides", C.c_int64 * 3),
+                ("v_strides", C.c_int64 * 3)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load libzipvl.so from the package directory; raise if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise ZipvlError(-100, f"{path} is missing: build it with `python -m paper_2410_08584_amd.build` "
+                               "(there is no CPU fallback)")
+    lib = C.CDLL(path)
+    vp, i32p, f32p = C.c_void_p, C.c_void_p, C.c_void_p
+    lib.zipvl_version.restype = C.c_int
+    lib.zipvl_last_error.restype = C.c_char_p
+    lib.zipvl_workspace_bytes.restype = C.c_size_t
+    lib.zipvl_workspace_bytes.argtypes = [C.c_int, C.POINTER(Dims), C.c_int]
+    lib.zipvl_score.argtypes = [vp, vp, C.POINTER(Dims), C.POINTER(C.c_int32), C.c_int, C.c_float,
+                                f32p, f32p, vp, C.c_size_t, vp]
+    lib.zipvl_select.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_double, i32p, i32p, vp, C.c_size_t, vp]
+    lib.zipvl_sparse_prefill.argtypes = [vp, vp, vp, C.POINTER(Dims), i32p, i32p, C.c_float, C.c_int,
+                                         vp, vp, C.c_size_t, vp]
+    lib.zipvl_compact_kv.argtypes = [vp, vp, C.POINTER(Dims), i32p, i32p, vp, vp, C.c_int32, i32p, vp]
+    lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
+    lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
+                                      C.c_size_t, vp]
+    for name in ("zipvl_score", "zipvl_select", "zipvl_sparse_prefill", "zipvl_compact_kv",
+                 "zipvl_kv_append", "zipvl_decode_attn"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def zipvl_version() -> int:
+    return int(load_library().zipvl_version())
+
+
+def zipvl_last_error() -> str:
+    return load_library().zipvl_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise ZipvlError(rc, zipvl_last_error())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return 0
+    if t.dtype == torch.bfloat16:
+        return 1
+    raise ZipvlError(-5, f"unsupported tensor dtype {t.dtype}")
+
+
+def _strides3(t: Optional[torch.Tensor]) -> Tuple[int, int, int]:
+    if t is None:
+        return (0, 0, 0)
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ZipvlError(-1, "expected a [B,H,n,d] view with a contiguous last dimension")
+    return (t.stride(0), t.stride(1), t.stride(2))
+
+
+def dims_of(Q: Optional[torch.Tensor], K: Optional[torch.Tensor], V: Optional[torch.Tensor] = None, *,
+            B=None, Hq=None, Hkv=None, n=None, d=None, dtype=None) -> Dims:
+    """Fill a zipvl_dims from [B,H,n,d] tensors (any memory order with d contiguous)."""
+    ref = Q if Q is not None else K
+    dm = Dims()
+    dm.B = B if B is not None else ref.shape[0]
+    dm.Hq = Hq if Hq is not None else (Q.shape[1] if Q is not None else K.shape[1])
+    dm.Hkv = Hkv if Hkv is not None else (K.shape[1] if K is not None else dm.Hq)
+    dm.n = n if n is not None else ref.shape[2]
+    dm.d = d if d is not None else ref.shape[3]
+    dm.dtype = dtype if dtype is not None else _dtype_code(ref)
+    dm.q_strides = (C.c_int64 * 3)(*_strides3(Q))
+    dm.k_strides = (C.c_int64 * 3)(*_strides3(K))
+    dm.v_strides = (C.c_int64 * 3)(*_strides3(V))
+    return dm
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def workspace_bytes(op: int, dims: Dims, m: int = 0) -> int:
+    return int(load_library().zipvl_workspace_bytes(op, C.byref(dims), m))
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def zipvl_score(Q: torch.Tensor, K: torch.Tensor, probe_pos: Sequence[int], softmax_scale: float, *,
+                mass: Optional[torch.Tensor] = None, rank: Optional[torch.Tensor] = None,
+                want_rank: bool = True, ws: Optional[torch.Tensor] = None):
+    """(mass, rank) fp32 [B*Hkv, n] from the probe rows of Q against K."""
+    lib = load_library()
+    dm = dims_of(Q, K)
+    units = dm.B * dm.Hkv
+    pp = [int(p) for p in probe_pos]
+    arr = (C.c_int32 * max(len(pp), 1))(*pp)
+    if mass is None:
+        mass = torch.empty((units, dm.n), dtype=torch.float32, device=Q.device)
+    if rank is None and want_rank:
+        rank = torch.empty((units, dm.n), dtype=torch.float32, device=Q.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SCORE, dm, len(pp)), Q.device)
+    _check(lib.zipvl_score(_ptr(Q), _ptr(K), C.byref(dm), arr, len(pp), float(softmax_scale),
+                           _ptr(mass), _ptr(rank), _ptr(ws), ws.numel(), _stream()))
+    return mass, rank
+
+
+def zipvl_select(mass: torch.Tensor, rank: Optional[torch.Tensor], tau: float, *,
+                 idx: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None):
+    """(idx [units,n] int32 with the first k entries valid and ascending, k [units] int32)."""
+    lib = load_library()
+    units, n = mass.shape
+    if idx is None:
+        idx = torch.empty((units, n), dtype=torch.int32, device=mass.device)
+    if k is None:
+        k = torch.empty((units,), dtype=torch.int32, device=mass.device)
+    _check(lib.zipvl_select(_ptr(mass), _ptr(rank), units, n, float(tau), _ptr(idx), _ptr(k), None, 0, _stream()))
+    return idx, k
+
+
+def zipvl_sparse_prefill(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, idx: Optional[torch.Tensor],
+                         k: Optional[torch.Tensor], softmax_scale: float, flags: int = OUT_FULL, *,
+                         O: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """O [B,Hq,n,d]: causal attention over the kept tokens (idx=k=None: all tokens)."""
+    lib = load_library()
+    dm = dims_of(Q, K, V)
+    if O is None:
+        O = torch.empty((dm.B, dm.Hq, dm.n, dm.d), dtype=Q.dtype, device=Q.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SPARSE_PREFILL, dm), Q.device)
+    _check(lib.zipvl_sparse_prefill(_ptr(Q), _ptr(K), _ptr(V), C.byref(dm), _ptr(idx), _ptr(k),
+                                    float(softmax_scale), int(flags), _ptr(O), _ptr(ws), ws.numel(), _stream()))
+    return O
+
+
+def zipvl_compact_kv(K: torch.Tensor, V: torch.Tensor, idx: Optional[torch.Tensor], k: Optional[torch.Tensor],
+                     cap: int, *, Kc: Optional[torch.Tensor] = None, Vc: Optional[torch.Tensor] = None,
+                     length: Optional[torch.Tensor] = None):
+    """(Kc, Vc [B*Hkv, cap, d], len [B*Hkv] int32): the evicted cache."""
+    lib = load_library()
+    dm = dims_of(None, K, V, Hq=K.shape[1])
+    units = dm.B * dm.Hkv
+    if Kc is None:
+        Kc = torch.empty((units, cap, dm.d), dtype=K.dtype, device=K.device)
+    if Vc is None:
+        Vc = torch.empty((units, cap, dm.d), dtype=K.dtype, device=K.device)
+    if length is None:
+        length = torch.empty((units,), dtype=torch.int32, device=K.device)
+    _check(lib.zipvl_compact_kv(_ptr(K), _ptr(V), C.byref(dm), _ptr(idx), _ptr(k), _ptr(Kc), _ptr(Vc),
+                                int(cap), _ptr(length), _stream()))
+    return Kc, Vc, length
+
+
+def zipvl_kv_append(Kc: torch.Tensor, Vc: torch.Tensor, length: torch.Tensor, k_new: torch.Tensor,
+                    v_new: torch.Tensor, *, B: int, Hkv: int):
+    lib = load_library()
+    units, cap, d = Kc.shape
+    dm = dims_of(None, None, None, B=B, Hq=Hkv, Hkv=Hkv, n=cap, d=d, dtype=_dtype_code(Kc))
+    _check(lib.zipvl_kv_append(_ptr(Kc), _ptr(Vc), _ptr(length), int(cap), _ptr(k_new), _ptr(v_new),
+                               C.byref(dm), _stream()))
+    return length
+
+
+def zipvl_decode_attn(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, length: torch.Tensor,
+                      softmax_scale: float, *, B: int, Hq: int, Hkv: int,
+                      o: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """o [B*Hq, d]: one query per head against the first len[u] cached rows."""
+    lib = load_library()
+    units, cap, d = Kc.shape
+    dm = dims_of(None, None, None, B=B, Hq=Hq, Hkv=Hkv, n=cap, d=d, dtype=_dtype_code(Kc))
+    if o is None:
+        o = torch.empty((B * Hq, d), dtype=q.dtype, device=q.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_DECODE, dm), q.device)
+    _check(lib.zipvl_decode_attn(_ptr(q), _ptr(Kc), _ptr(Vc), _ptr(length), int(cap), C.byref(dm),
+                                 float(softmax_scale), _ptr(o), _ptr(ws), ws.numel(), _stream()))
+    return o

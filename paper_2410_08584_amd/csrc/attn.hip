@@ -1,0 +1,333 @@
+// Attention over the kept tokens (Section 4.2; Algorithm 1, sparse-attention
+// step; Eq. (2) restricted to the important set T).
+//
+// Two kernels:
+//   pack   gathers K[T] row-major and V[T] transposed ([d][64 keys] tiles) into
+//          the workspace, once per KV head, zero-filling the ragged tail.  The
+//          transposed V is what lets the P.V product read both MFMA operands
+//          as contiguous fragments (the contraction runs over keys).
+//   flash  one workgroup = 128 kept queries of one query head (4 waves x 32
+//          rows).  K / V^T tiles of 64 keys are staged through LDS (double
+//          buffered, one barrier per tile) and shared by the four waves.
+//          S^T = K Q^T and O^T = V^T P^T are taken on 32x32 MFMA tiles, so a
+//          lane owns one query column: the online-softmax statistics are
+//          per-lane scalars and only the running maximum crosses lanes (one
+//          exchange between the two half-waves per tile).  Causality is the
+//          plain lower triangle in kept-token coordinates because T is
+//          ascending.  Query rows are gathered by idx on load and output rows
+//          are scattered by idx on store.
+// The kept count k lives on the device: the grid covers the worst case (k = n)
+// and workgroups beyond a unit's k exit at once; heavy (late) query tiles are
+// scheduled first.
+#include "launch.h"
+
+namespace zipvl {
+
+constexpr int kBM = 128;     // queries per workgroup
+constexpr int kBN = 64;      // keys per tile
+
+template <typename T, int D>
+struct AttnCfg {
+    static constexpr int E = Elem<T>::kBytes;
+    static constexpr int CH = D / Elem<T>::kPerChunk;       // Q/K fragments per row per lane
+    static constexpr int ODB = D / 32;                       // 32-row blocks of O^T
+    static constexpr int KS = D * E + 16;                    // LDS row stride of the K tile (bytes)
+    static constexpr int VS = kBN * E + 16;                  // LDS row stride of the V^T tile (bytes)
+    static constexpr int KCPR = D * E / 16;                  // 16-byte chunks per K row
+    static constexpr int VCPR = kBN * E / 16;                // 16-byte chunks per V^T row
+    static constexpr int CPT = kBN * D * E / 16 / 256;       // chunks per thread per tile (K or V^T)
+    static constexpr int K_TILE = kBN * KS;
+    static constexpr int V_TILE = D * VS;
+    static constexpr int LDS_BYTES = 2 * (K_TILE + V_TILE);
+};
+
+// ------------------------------------------------------------------ pack
+template <typename T, int D>
+__global__ __launch_bounds__(256) void pack_kv_kernel(
+    const T* __restrict__ K, const T* __restrict__ V,
+    int64_t ks0, int64_t ks1, int64_t ks2, int64_t vs0, int64_t vs1, int64_t vs2,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
+    T* __restrict__ Kp, T* __restrict__ VTp, int n, int npad, int Hkv, int rows_are_kept)
+{
+    constexpr int EPF = Elem<T>::kPerFrag;
+    constexpr int CPR = D / EPF;
+    constexpr int LS = D + EPF;                 // padded LDS row (elements)
+    __shared__ __attribute__((aligned(16))) T tile[kBN * LS];
+    const int u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
+    const int t0 = blockIdx.x * kBN;
+    int kk = kcnt ? kcnt[u] : n;
+    kk = max(0, min(kk, n));
+    if (t0 >= kk) return;
+    const T* Kb = K + b * ks0 + g * ks1;
+    const T* Vb = V + b * vs0 + g * vs1;
+    for (int wi = threadIdx.x; wi < kBN * CPR; wi += 256) {
+        const int r = wi / CPR, cc = wi - r * CPR, row = t0 + r;
+        uintx4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+        if (row < kk) {
+            const int src = (idx && !rows_are_kept) ? idx[(int64_t)u * n + row] : row;
+            kv = load16(Kb + (int64_t)src * ks2 + cc * EPF);
+            vv = load16(Vb + (int64_t)src * vs2 + cc * EPF);
+        }
+        store16(Kp + ((int64_t)u * npad + row) * D + cc * EPF, kv);
+        store16(tile + r * LS + cc * EPF, vv);
+    }
+    __syncthreads();
+    T* VT = VTp + ((int64_t)u * (npad / kBN) + blockIdx.x) * (D * kBN);
+    for (int wi = threadIdx.x; wi < D * (kBN / EPF); wi += 256) {
+        const int dd = wi % D, kc = wi / D;
+        T v[EPF];
+#pragma unroll
+        for (int e = 0; e < EPF; ++e) v[e] = tile[(kc * EPF + e) * LS + dd];
+        store16(VT + dd * kBN + kc * EPF, *reinterpret_cast<const uintx4*>(v));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void zero_fill_kernel(uintx4* __restrict__ p, int64_t n16) {
+    const uintx4 z = {0, 0, 0, 0};
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) p[i] = z;
+}
+
+// ------------------------------------------------------------------ flash
+template <typename T, int D>
+__device__ __forceinline__ void load_tile(const char* kt, const char* vt, int tid,
+                                          uintx4 (&kr)[AttnCfg<T, D>::CPT], uintx4 (&vr)[AttnCfg<T, D>::CPT]) {
+#pragma unroll
+    for (int q = 0; q < AttnCfg<T, D>::CPT; ++q) {
+        kr[q] = load16(kt + (q * 256 + tid) * 16);
+        vr[q] = load16(vt + (q * 256 + tid) * 16);
+    }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void stage_tile(char* ks, char* vs, int tid,
+                                           const uintx4 (&kr)[AttnCfg<T, D>::CPT], const uintx4 (&vr)[AttnCfg<T, D>::CPT]) {
+    using C = AttnCfg<T, D>;
+#pragma unroll
+    for (int q = 0; q < C::CPT; ++q) {
+        const int id = q * 256 + tid;
+        store16(ks + (id / C::KCPR) * C::KS + (id % C::KCPR) * 16, kr[q]);
+        store16(vs + (id / C::VCPR) * C::VS + (id % C::VCPR) * 16, vr[q]);
+    }
+}
+
+// P^T (32 keys x 32 queries block `blk`, registers p[16]) times V^T tile -> O^T accumulators.
+template <typename T, int D> struct PV;
+
+template <int D> struct PV<__bf16, D> {
+    __device__ static __forceinline__ void run(const char* vs, int i, int h, int blk, const float (&p)[16],
+                                               floatx16 (&o)[AttnCfg<__bf16, D>::ODB]) {
+        using C = AttnCfg<__bf16, D>;
+#pragma unroll
+        for (int a2 = 0; a2 < 2; ++a2) {
+            // contraction slot t of this lane <-> key 32*blk + 16*a2 + 8*(t/4) + 4*h + t%4
+            uintx4 bfrag;
+            bfrag[0] = pack_bf16x2(p[8 * a2 + 0], p[8 * a2 + 1]);
+            bfrag[1] = pack_bf16x2(p[8 * a2 + 2], p[8 * a2 + 3]);
+            bfrag[2] = pack_bf16x2(p[8 * a2 + 4], p[8 * a2 + 5]);
+            bfrag[3] = pack_bf16x2(p[8 * a2 + 6], p[8 * a2 + 7]);
+            const int koff = (32 * blk + 16 * a2 + 4 * h) * 2;
+#pragma unroll
+            for (int db = 0; db < C::ODB; ++db) {
+                const char* row = vs + (db * 32 + i) * C::VS + koff;
+                const uintx2 lo = *reinterpret_cast<const uintx2*>(row);
+                const uintx2 hi = *reinterpret_cast<const uintx2*>(row + 16);
+                const uintx4 afrag = {lo[0], lo[1], hi[0], hi[1]};
+                o[db] = mma_frag<__bf16>(afrag, bfrag, o[db]);
+            }
+        }
+    }
+};
+
+template <int D> struct PV<float, D> {
+    __device__ static __forceinline__ void run(const char* vs, int i, int h, int blk, const float (&p)[16],
+                                               floatx16 (&o)[AttnCfg<float, D>::ODB]) {
+        using C = AttnCfg<float, D>;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            // step (a, t): this lane contributes key 32*blk + 8*a + 4*h + t
+            const int koff = (32 * blk + 8 * a + 4 * h) * 4;
+#pragma unroll
+            for (int db = 0; db < C::ODB; ++db) {
+                const floatx4 v = *reinterpret_cast<const floatx4*>(vs + (db * 32 + i) * C::VS + koff);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(v[t], p[4 * a + t], o[db], 0, 0, 0);
+            }
+        }
+    }
+};
+
+template <typename T> __device__ __forceinline__ void store_out4(T* dst, float a, float b, float c, float d);
+template <> __device__ __forceinline__ void store_out4<float>(float* dst, float a, float b, float c, float d) {
+    *reinterpret_cast<floatx4*>(dst) = floatx4{a, b, c, d};
+}
+template <> __device__ __forceinline__ void store_out4<__bf16>(__bf16* dst, float a, float b, float c, float d) {
+    *reinterpret_cast<uintx2*>(dst) = uintx2{pack_bf16x2(a, b), pack_bf16x2(c, d)};
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void flash_kept_kernel(
+    const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
+    const T* __restrict__ Kp, const T* __restrict__ VTp,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
+    T* __restrict__ O, int n, int npad, int Hq, int Hkv, float c, int out_compact)
+{
+    using C = AttnCfg<T, D>;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tile_q = gridDim.x - 1 - blockIdx.x;          // heavy tiles first
+    const int i0 = tile_q * kBM;
+    const int bh = blockIdx.y, b = bh / Hq, head = bh - b * Hq;
+    const int G = Hq / Hkv, g = head / G, u = b * Hkv + g;
+    int kk = kcnt ? kcnt[u] : n;
+    kk = max(0, min(kk, n));
+    if (i0 >= kk) return;
+
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
+    const int qrow = i0 + 32 * w + i;                        // kept-token coordinate of this lane's query
+    const int qclamp = min(qrow, kk - 1);
+    const int qpos = idx ? idx[(int64_t)u * n + qclamp] : qclamp;
+
+    uintx4 qf[C::CH];
+    {
+        const T* qp = Q + b * qs0 + head * qs1 + (int64_t)qpos * qs2;
+#pragma unroll
+        for (int cc = 0; cc < C::CH; ++cc) qf[cc] = load16(qp + cc * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
+    }
+    floatx16 o[C::ODB];
+#pragma unroll
+    for (int db = 0; db < C::ODB; ++db) o[db] = floatx16{0};
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int ntiles = (min(i0 + kBM, kk) + kBN - 1) / kBN;
+    const int wave_first_row = i0 + 32 * w, wave_last_row = wave_first_row + 31;
+    const char* kg = reinterpret_cast<const char*>(Kp + (int64_t)u * npad * D);
+    const char* vg = reinterpret_cast<const char*>(VTp + (int64_t)u * npad * D);
+    constexpr int TILE_BYTES = kBN * D * C::E;
+
+    uintx4 kr[C::CPT], vr[C::CPT];
+    load_tile<T, D>(kg, vg, tid, kr, vr);
+    for (int t = 0; t < ntiles; ++t) {
+        char* ks = smem + (t & 1) * (C::K_TILE + C::V_TILE);
+        char* vs = ks + C::K_TILE;
+        stage_tile<T, D>(ks, vs, tid, kr, vr);
+        __syncthreads();
+        if (t + 1 < ntiles)
+            load_tile<T, D>(kg + (int64_t)(t + 1) * TILE_BYTES, vg + (int64_t)(t + 1) * TILE_BYTES, tid, kr, vr);
+        const int t0 = t * kBN;
+        if (t0 > wave_last_row) continue;                    // whole tile is in this wave's future
+
+        // S^T block blk: keys t0 + 32*blk + acc_row(r, h), query column = this lane's
+        float p[2][16];
+        float mx = -INFINITY;
+        const bool need_mask = t0 + kBN - 1 > wave_first_row;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            floatx16 acc = {0};
+#pragma unroll
+            for (int cc = 0; cc < C::CH; ++cc) {
+                const uintx4 a = *reinterpret_cast<const uintx4*>(ks + (blk * 32 + i) * C::KS + cc * 32 + h * 16);
+                acc = mma_frag<T>(a, qf[cc], acc);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float s = acc[r] * c;
+                if (need_mask && t0 + 32 * blk + acc_row(r, h) > qrow) s = -INFINITY;
+                p[blk][r] = s;
+                mx = fmaxf(mx, s);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);                // finite: key 0 is visible to every row
+        const float alpha = fast_exp2(m_run - m_new);
+        float sum = 0.f;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                p[blk][r] = fast_exp2(p[blk][r] - m_new);
+                sum += p[blk][r];
+            }
+        l_run = l_run * alpha + sum;
+        m_run = m_new;
+#pragma unroll
+        for (int db = 0; db < C::ODB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) PV<T, D>::run(vs, i, h, blk, p[blk], o);
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (qrow < kk) {
+        const float inv = 1.f / l_tot;
+        const int orow = out_compact ? qrow : qpos;
+        T* op = O + ((int64_t)bh * n + orow) * D;
+#pragma unroll
+        for (int db = 0; db < C::ODB; ++db)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+                store_out4<T>(op + 32 * db + 8 * a + 4 * h, o[db][4 * a] * inv, o[db][4 * a + 1] * inv,
+                              o[db][4 * a + 2] * inv, o[db][4 * a + 3] * inv);
+    }
+}
+
+// ------------------------------------------------------------------ host
+size_t prefill_workspace_bytes(const zipvl_dims& d) {
+    const int e = d.dtype == ZIPVL_BF16 ? 2 : 4;
+    const size_t npad = ((size_t)d.n + kBN - 1) / kBN * kBN;
+    return 2 * (size_t)d.B * d.Hkv * npad * d.d * e;
+}
+
+template <typename T, int D>
+static int launch_prefill_t(const void* Q, const void* K, const void* V, const zipvl_dims& d,
+                            const int32_t* idx, const int32_t* k, float scale, int flags,
+                            void* O, void* ws, hipStream_t st)
+{
+    using C = AttnCfg<T, D>;
+    const int npad = (d.n + kBN - 1) / kBN * kBN;
+    const int units = d.B * d.Hkv;
+    T* Kp = (T*)ws;
+    T* VTp = Kp + (size_t)units * npad * D;
+    const int out_compact = (flags & ZIPVL_OUT_COMPACT) ? 1 : 0;
+    const int rows_are_kept = (flags & ZIPVL_KV_ALREADY_COMPACT) ? 1 : 0;
+
+    if (!out_compact && idx) {
+        const int64_t n16 = (int64_t)d.B * d.Hq * d.n * D * C::E / 16;
+        const int blocks = (int)(n16 / 256 / 4 < 1 ? 1 : (n16 / 256 / 4 > 8192 ? 8192 : n16 / 256 / 4));
+        hipLaunchKernelGGL((zero_fill_kernel<T>), dim3(blocks), dim3(256), 0, st, (uintx4*)O, n16);
+        int rc = check_launch("zero_fill");
+        if (rc) return rc;
+    }
+    hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kBN, units), dim3(256), 0, st,
+        (const T*)K, (const T*)V, d.k_strides[0], d.k_strides[1], d.k_strides[2],
+        d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept);
+    int rc = check_launch("pack_kv");
+    if (rc) return rc;
+
+    static bool attr_done = false;       // raising the dynamic-LDS cap is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kept_kernel<T, D>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
+            return set_error(ZIPVL_EHIP, "sparse_prefill: cannot reserve %d bytes of LDS", C::LDS_BYTES);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((d.n + kBM - 1) / kBM, d.B * d.Hq), dim3(256),
+        C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
+        (const T*)Kp, (const T*)VTp, idx, k, (T*)O, d.n, npad, d.Hq, d.Hkv, scale * kLog2e, out_compact);
+    return check_launch("flash_kept");
+}
+
+int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims& d,
+                          const int32_t* idx, const int32_t* k, float scale, int flags,
+                          void* O, void* ws, hipStream_t st)
+{
+    if (d.dtype == ZIPVL_BF16) {
+        if (d.d == 128) return launch_prefill_t<__bf16, 128>(Q, K, V, d, idx, k, scale, flags, O, ws, st);
+        return launch_prefill_t<__bf16, 64>(Q, K, V, d, idx, k, scale, flags, O, ws, st);
+    }
+    if (d.d == 128) return launch_prefill_t<float, 128>(Q, K, V, d, idx, k, scale, flags, O, ws, st);
+    return launch_prefill_t<float, 64>(Q, K, V, d, idx, k, scale, flags, O, ws, st);
+}
+
+}  // namespace zipvl

@@ -1,0 +1,32 @@
+// Host-side launch entry points of each kernel file (internal to the library).
+#pragma once
+#include "common.h"
+
+namespace zipvl {
+
+struct ProbeList {            // passed by value in the kernel arguments
+    int32_t pos[ZIPVL_MAX_PROBES];
+};
+
+size_t score_workspace_bytes(const zipvl_dims& d, int m);
+int launch_score(const void* Q, const void* K, const zipvl_dims& d, const int32_t* probe_pos, int m,
+                 float scale, float* mass, float* rank, void* ws, hipStream_t st);
+
+int launch_select(const float* mass, const float* rank, int units, int n, double tau,
+                  int32_t* idx, int32_t* k, hipStream_t st);
+
+size_t prefill_workspace_bytes(const zipvl_dims& d);
+int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims& d,
+                          const int32_t* idx, const int32_t* k, float scale, int flags,
+                          void* O, void* ws, hipStream_t st);
+
+int launch_compact_kv(const void* K, const void* V, const zipvl_dims& d, const int32_t* idx,
+                      const int32_t* k, void* Kc, void* Vc, int32_t cap, int32_t* len, hipStream_t st);
+int launch_kv_append(void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
+                     const void* v_new, const zipvl_dims& d, hipStream_t st);
+
+size_t decode_workspace_bytes(const zipvl_dims& d, int cap);
+int launch_decode_attn(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
+                       const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);
+
+}  // namespace zipvl

@@ -1,0 +1,246 @@
+// Adaptive count and important-token set (Eq. (7), Eq. (9); Algorithm 1 steps 3-5).
+//
+// The definition is "sort descending, cumulative sum, first crossing of
+// tau * total, then top-k by the normalised score".  Neither step needs the
+// sorted sequence itself:
+//   * the first crossing of the sorted cumulative sum is found by a radix
+//     descent over the 32-bit order-preserving image of the fp32 scores: per
+//     8-bit digit, an LDS histogram of counts and of exact integer sums
+//     (floor(x * 2^40), so the result is independent of summation order),
+//     a descending wave-shuffle scan over the 256 bins, and the bin where the
+//     running sum crosses the target; after four digits the remaining
+//     candidates are equal and the count follows by one integer division;
+//   * the top-k set is {score > v*} plus the lowest-indexed ties at v*, where
+//     v* is the k-th largest value, found by the same descent on counts;
+//   * the set is written in ascending position by a ballot-ranked stream
+//     compaction (each wave owns a contiguous span of positions).
+// One 1024-thread workgroup per selection unit; the score vectors stay in L2
+// (72 KB per vector at n = 18432) and are re-read once per digit.
+#include "launch.h"
+
+namespace zipvl {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kRep = 16;              // histogram replicas (lane % 16) against same-address atomics
+
+struct SelShared {
+    uint32_t cnt[256 * kRep];
+    unsigned long long sum[256 * kRep];
+    uint32_t bin_cnt[256];
+    unsigned long long bin_sum[256];
+    unsigned long long target;
+    unsigned long long base_sum;
+    uint32_t base_cnt;
+    uint32_t sel_digit;
+    uint32_t wave_gt[kSelWaves];
+    uint32_t wave_eq[kSelWaves];
+    int k;
+};
+
+// Order-preserving map fp32 -> uint32 (larger float <=> larger key); -0 and +0 coincide.
+__device__ __forceinline__ uint32_t orderable(float x) {
+    uint32_t b = __float_as_uint(x);
+    if ((b << 1) == 0) b = 0;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// floor(x * 2^40) for finite x in [0, 2^24), exact, integer-only.
+__device__ __forceinline__ unsigned long long fixed40(float x) {
+    const uint32_t b = __float_as_uint(x);
+    const int e = (b >> 23) & 255;
+    if ((b & 0x80000000u) || e == 0 || e == 255) return 0ull;
+    const unsigned long long M = (b & 0x7FFFFFu) | 0x800000u;     // x = M * 2^(e-150)
+    const int sh = e - 110;
+    if (sh >= 0) return M << (sh > 40 ? 40 : sh);
+    return (-sh >= 24) ? 0ull : (M >> (-sh));
+}
+
+// One descent over the four 8-bit digits.  WITH_SUM: cross on the integer sum
+// (target = sh.target, fixed after the first digit from the grand total);
+// otherwise cross on the element count (target = cnt_target).
+template <bool WITH_SUM>
+__device__ void radix_descent(const float* __restrict__ x, int n, double tau, uint32_t cnt_target,
+                              SelShared& sh, uint32_t& prefix_out, uint32_t& base_cnt_out,
+                              unsigned long long& base_sum_out, bool& degenerate)
+{
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, mask = 0, base_cnt = 0;
+    unsigned long long base_sum = 0;
+    degenerate = false;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int i = tid; i < 256 * kRep; i += kSelThreads) {
+            sh.cnt[i] = 0;
+            if (WITH_SUM) sh.sum[i] = 0;
+        }
+        __syncthreads();
+        for (int j = tid; j < n; j += kSelThreads) {
+            const float v = x[j];
+            const uint32_t key = orderable(v);
+            if ((key & mask) == prefix) {
+                const int slot = ((key >> shift) & 255) * kRep + (tid & (kRep - 1));
+                atomicAdd(&sh.cnt[slot], 1u);
+                if (WITH_SUM) atomicAdd(&sh.sum[slot], fixed40(v));
+            }
+        }
+        __syncthreads();
+        if (tid < 256) {
+            uint32_t c = 0;
+            unsigned long long s = 0;
+#pragma unroll
+            for (int r = 0; r < kRep; ++r) {
+                c += sh.cnt[tid * kRep + r];
+                if (WITH_SUM) s += sh.sum[tid * kRep + r];
+            }
+            sh.bin_cnt[tid] = c;
+            sh.bin_sum[tid] = s;
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane l scans bins 255-4l .. 252-4l (descending value order)
+            uint32_t c[4], lc = 0;
+            unsigned long long s[4], ls = 0;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                c[t] = sh.bin_cnt[255 - (4 * tid + t)];
+                s[t] = WITH_SUM ? sh.bin_sum[255 - (4 * tid + t)] : 0ull;
+                lc += c[t];
+                ls += s[t];
+            }
+            uint32_t ic = lc;
+            unsigned long long is = ls;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t tc = __shfl_up(ic, o);
+                const unsigned long long ts = __shfl_up(is, o);
+                if (tid >= o) { ic += tc; is += ts; }
+            }
+            unsigned long long target;
+            if (WITH_SUM) {
+                if (pass == 0) {
+                    const unsigned long long W = __shfl(is, 63);
+                    // ceil(tau * W): one IEEE double multiply, then ceil (W < 2^53)
+                    const double prod = tau * (double)W;
+                    target = (unsigned long long)ceil(prod);
+                    if (tid == 0) sh.target = target;
+                } else {
+                    target = sh.target;
+                }
+            } else {
+                target = cnt_target;
+            }
+            uint32_t rc = base_cnt + (ic - lc);
+            unsigned long long rs = base_sum + (is - ls);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const bool cross = WITH_SUM ? (rs < target && target <= rs + s[t])
+                                            : ((unsigned long long)rc < target && target <= (unsigned long long)rc + c[t]);
+                if (cross) {
+                    sh.sel_digit = 255 - (4 * tid + t);
+                    sh.base_cnt = rc;
+                    sh.base_sum = rs;
+                }
+                rc += c[t];
+                rs += s[t];
+            }
+        }
+        __syncthreads();
+        if (WITH_SUM && sh.target == 0ull) { degenerate = true; break; }   // all scores zero
+        prefix |= sh.sel_digit << shift;
+        mask |= 255u << shift;
+        base_cnt = sh.base_cnt;
+        base_sum = sh.base_sum;
+    }
+    prefix_out = prefix;
+    base_cnt_out = base_cnt;
+    base_sum_out = base_sum;
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(
+    const float* __restrict__ mass_all, const float* __restrict__ rank_all, int n, double tau,
+    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out)
+{
+    __shared__ SelShared sh;
+    const int u = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* mass = mass_all + (int64_t)u * n;
+    const float* rank = rank_all ? rank_all + (int64_t)u * n : mass;
+    int32_t* idx = idx_all + (int64_t)u * n;
+
+    // ---- how many (Eq. (7)) ----
+    int k;
+    if (tau >= 1.0) {
+        k = n;
+    } else {
+        uint32_t prefix, base_cnt;
+        unsigned long long base_sum;
+        bool degenerate;
+        radix_descent<true>(mass, n, tau, 0u, sh, prefix, base_cnt, base_sum, degenerate);
+        if (tid == 0) {
+            int kk = 1;
+            if (!degenerate) {
+                const unsigned long long qv = fixed40(__uint_as_float(prefix ^ 0x80000000u));
+                const unsigned long long need = sh.target - base_sum;           // >= 1
+                kk = (int)(base_cnt + (qv ? (need + qv - 1) / qv : 1ull));
+            }
+            sh.k = max(1, min(kk, n));
+        }
+        __syncthreads();
+        k = sh.k;
+    }
+    if (tid == 0) k_out[u] = k;
+    if (k >= n) {
+        for (int j = tid; j < n; j += kSelThreads) idx[j] = j;
+        return;
+    }
+    __syncthreads();
+
+    // ---- which (Eq. (9)): k-th largest normalised score v*, ties to the lower index ----
+    uint32_t vstar, cnt_gt;
+    {
+        unsigned long long unused;
+        bool dg;
+        radix_descent<false>(rank, n, tau, (uint32_t)k, sh, vstar, cnt_gt, unused, dg);
+    }
+    const uint32_t need_eq = (uint32_t)k - cnt_gt;     // ties at v* that are kept (>= 1)
+
+    // ---- ascending emission: wave w owns positions [w*seg, (w+1)*seg) ----
+    const int seg = (((n + kSelWaves - 1) / kSelWaves) + 63) & ~63;
+    const int j0 = wave * seg, j1 = min(n, j0 + seg);
+    uint32_t wgt = 0, weq = 0;
+    for (int j = j0 + lane; j - lane < j1; j += 64) {
+        const uint32_t key = (j < j1) ? orderable(rank[j]) : 0u;
+        wgt += __popcll(__ballot(j < j1 && key > vstar));
+        weq += __popcll(__ballot(j < j1 && key == vstar));
+    }
+    if (lane == 0) { sh.wave_gt[wave] = wgt; sh.wave_eq[wave] = weq; }
+    __syncthreads();
+    uint32_t gt_before = 0, eq_before = 0;
+    for (int w = 0; w < wave; ++w) { gt_before += sh.wave_gt[w]; eq_before += sh.wave_eq[w]; }
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int j = j0 + lane; j - lane < j1; j += 64) {
+        const uint32_t key = (j < j1) ? orderable(rank[j]) : 0u;
+        const bool gt = j < j1 && key > vstar;
+        const bool eq = j < j1 && key == vstar;
+        const unsigned long long bg = __ballot(gt), be = __ballot(eq);
+        const uint32_t my_eq_rank = eq_before + __popcll(be & lt_mask);
+        const bool keep = gt || (eq && my_eq_rank < need_eq);
+        const unsigned long long bk = __ballot(keep);
+        if (keep) {
+            const uint32_t pos = gt_before + min(eq_before, need_eq) + __popcll(bk & lt_mask);
+            idx[pos] = j;
+        }
+        gt_before += __popcll(bg);
+        eq_before += __popcll(be);
+    }
+}
+
+int launch_select(const float* mass, const float* rank, int units, int n, double tau,
+                  int32_t* idx, int32_t* k, hipStream_t st)
+{
+    hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, st, mass, rank, n, tau, idx, k);
+    return check_launch("select");
+}
+
+}  // namespace zipvl

@@ -1,0 +1,361 @@
+"""Parity of the HIP path (through the C ABI) against the CPU float64 oracle.
+
+Rules: kept count and kept index set are exact when the oracle's selection is
+fed the GPU's own fp32 scores; scores within 1e-6 + 1e-3*value (bf16 inputs)
+or 1e-7 + 1e-5*value (fp32 inputs); attention outputs within max-abs 2e-2
+(bf16) / 1e-4 (fp32) with the oracle evaluated on the GPU's index set;
+compaction bit-exact.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2410_08584_amd as z
+from oracle import zipvl_oracle as oz
+from workloads import make_custom, make_workload
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ATOL_OUT = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(x32: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x32)).to(DEV)
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def host64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def score_tol(dtype):
+    return (1e-6, 1e-3) if dtype == "bf16" else (1e-7, 1e-5)
+
+
+def assert_scores_close(got, ref, dtype, what):
+    a, r = score_tol(dtype)
+    err = np.abs(got - ref) - (a + r * np.abs(ref))
+    assert err.max() <= 0, f"{what}: worst excess {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+# ------------------------------------------------------------------ compaction
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_compact_kv_bit_exact(dtype, d):
+    say(f"compact_kv dtype={dtype} d={d}")
+    B, Hkv, n, cap = 2, 3, 333, 300
+    r = np.random.Generator(np.random.PCG64(5))
+    w = make_custom(B, Hkv, Hkv, n, d, dtype, seed=11)
+    # token-major memory order [B,n,H,d] viewed as [B,H,n,d]
+    K = dev(w.K, dtype).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    V = dev(w.V, dtype)
+    ks = [1, 64, 65, 300, 7, 129]
+    idx = np.zeros((B * Hkv, n), dtype=np.int32)
+    for u, k in enumerate(ks):
+        idx[u, :k] = np.sort(r.choice(n, k, replace=False))
+    Kc, Vc, ln = z.zipvl_compact_kv(K, V, torch.from_numpy(idx).to(DEV),
+                                    torch.tensor(ks, dtype=torch.int32, device=DEV), cap)
+    torch.cuda.synchronize()
+    assert ln.cpu().tolist() == ks
+    Kc_h, Vc_h = Kc.to(torch.float32).cpu().numpy(), Vc.to(torch.float32).cpu().numpy()
+    for u, k in enumerate(ks):
+        b, g = divmod(u, Hkv)
+        ko, vo, _ = oz.compact_kv(w.K[b, g], w.V[b, g], idx[u, :k])
+        assert Kc_h[u, :k].tobytes() == ko.tobytes() and Vc_h[u, :k].tobytes() == vo.tobytes()
+    # all rows, and a cap smaller than k
+    Kc2, Vc2, ln2 = z.zipvl_compact_kv(K, V, None, None, 100)
+    torch.cuda.synchronize()
+    assert ln2.cpu().tolist() == [100] * (B * Hkv)
+    assert Kc2.to(torch.float32).cpu().numpy()[4].tobytes() == w.K[1, 1, :100].tobytes()
+
+
+# ------------------------------------------------------------------ selection
+def _select_case(name, mass, rank, tau):
+    say(f"select case={name} units={mass.shape[0]} n={mass.shape[1]} tau={tau}")
+    m_d = torch.from_numpy(mass).to(DEV)
+    r_d = None if rank is None else torch.from_numpy(rank).to(DEV)
+    idx, k = z.zipvl_select(m_d, r_d, tau)
+    torch.cuda.synchronize()
+    idx, k = idx.cpu().numpy(), k.cpu().numpy()
+    for u in range(mass.shape[0]):
+        p, T = oz.select(mass[u], None if rank is None else rank[u], tau)
+        assert k[u] == p, f"{name} unit {u}: k {k[u]} != {p}"
+        assert np.array_equal(idx[u, :p], T), f"{name} unit {u}: index set differs"
+
+
+def test_select_exact_on_synthetic_distributions():
+    r = np.random.Generator(np.random.PCG64(21))
+
+    def norm(x):
+        return (x / x.sum(axis=1, keepdims=True)).astype(np.float32)
+
+    for n in (1, 2, 63, 64, 65, 577, 1024, 4097, 18432):
+        skew = norm(r.random((3, n)) ** 8 + 1e-9)
+        rk = (skew * (1 + 0.5 * r.random((3, n)))).astype(np.float32)
+        _select_case(f"skew-n{n}", skew, rk, 0.975)
+        _select_case(f"skew-single-n{n}", skew, None, 0.9)
+    n = 3000
+    ties = norm(np.round(r.random((2, n)) * 6) + 1.0)            # 7 distinct values: many ties
+    _select_case("ties", ties, ties[:, ::-1].copy(), 0.7)
+    _select_case("ties-single", ties, None, 0.6180339887)
+    uni = np.full((2, 1000), 2.0 ** -10, dtype=np.float32)
+    for tau in (0.5, 0.975, 0.999, 1.0):
+        _select_case("uniform", uni, None, tau)
+    _select_case("zeros", np.zeros((2, 500), dtype=np.float32), None, 0.9)
+    onehot = np.zeros((2, 700), dtype=np.float32); onehot[0, 699] = 1.0; onehot[1, 0] = 1.0
+    _select_case("onehot", onehot, None, 0.99)
+    tiny = norm(r.random((2, 2048))) * np.float32(2.0 ** -30)      # most values below the 2^-40 grid step
+    _select_case("tiny", tiny.astype(np.float32), None, 0.95)
+    wide = norm(np.exp(r.normal(0, 6, (4, 8192))))                # many exponents
+    for tau in (0.3, 0.95, 0.975, 0.99, 0.99999):
+        _select_case("lognormal", wide, (wide * r.random((4, 8192))).astype(np.float32), tau)
+    # softmax-like: a few heavy tokens and a long tail, rank boosts the last 64 columns
+    tail = norm(np.concatenate([r.random((2, 40)) * 50, r.random((2, 18392)) * 0.01], axis=1))
+    rk = tail.copy(); rk[:, -64:] *= np.linspace(1, 64, 64, dtype=np.float32)
+    _select_case("heavy+tail", tail, rk, 0.975)
+
+
+# ------------------------------------------------------------------ scores
+SCORE_CASES = [
+    # B, Hq, Hkv, n, d, dtype, m, probe
+    (1, 4, 4, 576, 64, "f32", 64, None),
+    (2, 4, 2, 700, 128, "bf16", 64, None),
+    (1, 6, 2, 333, 64, "bf16", 24, None),
+    (1, 2, 1, 1500, 128, "f32", 64, None),
+    (1, 7, 1, 2100, 128, "bf16", 64, "scattered"),
+    (1, 2, 2, 70, 64, "f32", 64, None),
+]
+
+
+@pytest.mark.parametrize("case", SCORE_CASES, ids=lambda c: f"B{c[0]}Hq{c[1]}Hkv{c[2]}n{c[3]}d{c[4]}{c[5]}m{c[6]}{c[7] or ''}")
+def test_scores_match_oracle(case):
+    B, Hq, Hkv, n, d, dtype, m, probe = case
+    say(f"score case={case}")
+    pp = None
+    if probe == "scattered":
+        r = np.random.Generator(np.random.PCG64(3))
+        pp = np.sort(np.concatenate([r.choice(n - 200, m - 20, replace=False), np.arange(n - 20, n)])).astype(np.int32)
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=100 + n, m=m, probe_pos=pp)
+    Q, K = dev(w.Q, dtype), dev(w.K, dtype)
+    mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
+    torch.cuda.synchronize()
+    mass, rank = host64(mass).reshape(B, Hkv, n), host64(rank).reshape(B, Hkv, n)
+    for b in range(B):
+        mo, ro = oz.token_scores(w.Q[b], w.K[b], w.probe_pos, w.scale)
+        assert_scores_close(mass[b], mo, dtype, "mass")
+        assert_scores_close(rank[b], ro, dtype, "rank")
+        np.testing.assert_allclose(mass[b].sum(axis=1), 1.0, atol=2e-5)
+
+
+# ------------------------------------------------------------------ attention
+def _attention_case(B, Hq, Hkv, n, d, dtype, ks, seed=0, flags=0, dense=False):
+    G = Hq // Hkv
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=seed)
+    Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
+    units = B * Hkv
+    r = np.random.Generator(np.random.PCG64(seed + 1))
+    idx = np.zeros((units, n), dtype=np.int32)
+    for u in range(units):
+        idx[u, :ks[u]] = np.sort(r.choice(n, ks[u], replace=False))
+    if dense:
+        O = z.zipvl_sparse_prefill(Q, K, V, None, None, w.scale)
+    else:
+        O = torch.full((B, Hq, n, d), 7.0, dtype=Q.dtype, device=DEV)   # poison: dropped rows must be rewritten
+        z.zipvl_sparse_prefill(Q, K, V, torch.from_numpy(idx).to(DEV),
+                               torch.tensor(ks, dtype=torch.int32, device=DEV), w.scale, flags, O=O)
+    torch.cuda.synchronize()
+    Oh = host64(O)
+    worst = 0.0
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            u = b * Hkv + g
+            T = np.arange(n) if dense else idx[u, :ks[u]]
+            ref = oz.kept_token_attention(w.Q[b, h], w.K[b, g], w.V[b, g], T, w.scale,
+                                          compact_out=bool(flags & z.OUT_COMPACT))
+            got = Oh[b, h, :len(T)] if flags & z.OUT_COMPACT else Oh[b, h]
+            worst = max(worst, np.abs(got - ref).max())
+    say(f"  worst |dO| = {worst:.3e}")
+    assert worst <= ATOL_OUT[dtype]
+
+
+def test_attention_fp32_small_ragged():
+    say("attention fp32 d=64 ragged k")
+    _attention_case(1, 4, 4, 576, 64, "f32", [576, 1, 130, 67], seed=1)
+
+
+def test_attention_bf16_gqa_ragged():
+    say("attention bf16 d=128 GQA ragged k")
+    _attention_case(2, 6, 2, 700, 128, "bf16", [700, 257, 64, 385], seed=2)
+
+
+def test_attention_bf16_d64_and_fp32_d128():
+    say("attention bf16 d=64")
+    _attention_case(1, 2, 2, 300, 64, "bf16", [300, 129], seed=3)
+    say("attention fp32 d=128")
+    _attention_case(1, 2, 1, 260, 128, "f32", [200], seed=4)
+
+
+def test_attention_dense_mode_equals_dense_oracle():
+    say("attention dense (idx=k=NULL)")
+    _attention_case(1, 4, 2, 450, 128, "bf16", [450, 450], seed=5, dense=True)
+    _attention_case(1, 2, 2, 200, 64, "f32", [200, 200], seed=6, dense=True)
+
+
+def test_attention_compact_output_rows():
+    say("attention OUT_COMPACT")
+    _attention_case(1, 4, 2, 500, 128, "bf16", [333, 128], seed=7, flags=z.OUT_COMPACT)
+
+
+def test_attention_on_already_compacted_cache():
+    say("attention KV_ALREADY_COMPACT")
+    B, Hq, Hkv, n, d, dtype = 1, 4, 2, 400, 128, "bf16"
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=8)
+    Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
+    ks = [211, 77]
+    r = np.random.Generator(np.random.PCG64(9))
+    idx = np.zeros((2, n), dtype=np.int32)
+    for u in range(2):
+        idx[u, :ks[u]] = np.sort(r.choice(n, ks[u], replace=False))
+    idx_d, k_d = torch.from_numpy(idx).to(DEV), torch.tensor(ks, dtype=torch.int32, device=DEV)
+    Kc, Vc, _ = z.zipvl_compact_kv(K, V, idx_d, k_d, n)
+    O1 = z.zipvl_sparse_prefill(Q, K, V, idx_d, k_d, w.scale)
+    O2 = z.zipvl_sparse_prefill(Q, Kc.view(B, Hkv, n, d), Vc.view(B, Hkv, n, d), idx_d, k_d, w.scale,
+                                z.KV_ALREADY_COMPACT)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
+
+
+# ------------------------------------------------------------------ whole layer
+def _layer_parity(w, tau, sample_rows=None, heads=None):
+    spec = w.spec
+    B, Hq, Hkv, n, d, dtype = spec.B if w.Q.shape[0] == spec.B else w.Q.shape[0], spec.Hq, spec.Hkv, spec.n, spec.d, spec.dtype
+    G = Hq // Hkv
+    Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
+    mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
+    idx, k = z.zipvl_select(mass, rank, tau)
+    Kc, Vc, ln = z.zipvl_compact_kv(K, V, idx, k, n)
+    O = z.zipvl_sparse_prefill(Q, K, V, idx, k, w.scale)
+    torch.cuda.synchronize()
+    mass_h, rank_h = mass.cpu().numpy(), rank.cpu().numpy()
+    idx_h, k_h = idx.cpu().numpy(), k.cpu().numpy()
+    assert ln.cpu().tolist() == k_h.tolist()
+    kept = []
+    for b in range(B):
+        mo, ro = oz.token_scores(w.Q[b], w.K[b], w.probe_pos, w.scale)
+        assert_scores_close(mass_h.reshape(B, Hkv, n)[b].astype(np.float64), mo, dtype, "mass")
+        assert_scores_close(rank_h.reshape(B, Hkv, n)[b].astype(np.float64), ro, dtype, "rank")
+        for g in range(Hkv):
+            u = b * Hkv + g
+            p, T = oz.select(mass_h[u], rank_h[u], tau)             # oracle fed the GPU's fp32 scores
+            assert k_h[u] == p and np.array_equal(idx_h[u, :p], T), f"unit {u}: selection differs"
+            kept.append(p / n)
+            ko, vo, _ = oz.compact_kv(w.K[b, g], w.V[b, g], T)
+            assert Kc[u, :p].to(torch.float32).cpu().numpy().tobytes() == ko.tobytes()
+            assert Vc[u, :p].to(torch.float32).cpu().numpy().tobytes() == vo.tobytes()
+    worst = 0.0
+    r = np.random.Generator(np.random.PCG64(77))
+    for b in range(B):
+        for h in (range(Hq) if heads is None else heads):
+            g = h // G
+            u = b * Hkv + g
+            T = idx_h[u, :k_h[u]]
+            Oh = host64(O[b, h])
+            if sample_rows is None:
+                ref = oz.kept_token_attention(w.Q[b, h], w.K[b, g], w.V[b, g], T, w.scale)
+                worst = max(worst, np.abs(Oh - ref).max())
+            else:
+                rows = np.unique(np.concatenate([[0, len(T) - 1, min(127, len(T) - 1), min(128, len(T) - 1)],
+                                                 r.integers(0, len(T), sample_rows)]))
+                ref = oz.kept_token_attention_rows(w.Q[b, h], w.K[b, g], w.V[b, g], T, rows, w.scale)
+                worst = max(worst, np.abs(Oh[T[rows]] - ref).max())
+                dropped = np.setdiff1d(np.arange(n), T)
+                assert not Oh[dropped].any(), "dropped rows must be zero"
+    say(f"  kept {100 * np.mean(kept):.1f}% (min {100 * min(kept):.1f}, max {100 * max(kept):.1f}); worst |dO| = {worst:.3e}")
+    assert worst <= ATOL_OUT[dtype]
+    return kept
+
+
+def test_layer_cfg1_full():
+    say("layer cfg1 (fp32, n=576)")
+    w = make_workload(1)
+    _layer_parity(w, w.tau)
+
+
+def test_layer_tau_one_is_dense_attention():
+    say("layer tau=1")
+    w = make_custom(1, 4, 2, 320, 128, "bf16", seed=12)
+    Q, K, V = dev(w.Q, "bf16"), dev(w.K, "bf16"), dev(w.V, "bf16")
+    mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
+    idx, k = z.zipvl_select(mass, rank, 1.0)
+    O = z.zipvl_sparse_prefill(Q, K, V, idx, k, w.scale)
+    torch.cuda.synchronize()
+    assert k.cpu().tolist() == [320, 320]
+    for h in range(4):
+        ref = oz.dense_causal_attention(w.Q[0, h], w.K[0, h // 2], w.V[0, h // 2], w.scale)
+        assert np.abs(host64(O[0, h]) - ref).max() <= 2e-2
+
+
+def test_layer_cfg2_sampled():
+    say("layer cfg2 (bf16, 32 heads, n=3072), sampled output rows")
+    w = make_workload(2)
+    _layer_parity(w, w.tau, sample_rows=24, heads=[0, 13, 31])
+
+
+def test_layer_cfg3_three_taus_selection_and_sampled_rows():
+    say("layer cfg3 (bf16, 40 heads, n=4096)")
+    w = make_workload(3)
+    ks = []
+    for tau in w.spec.taus:
+        kept = _layer_parity(w, tau, sample_rows=8, heads=[7])
+        ks.append(np.mean(kept))
+    assert ks[0] <= ks[1] <= ks[2]
+
+
+def test_layer_cfg4_headline_shape_sampled():
+    say("layer cfg4 (bf16 GQA 28/4, n=18432), sampled output rows")
+    w = make_workload(4)
+    _layer_parity(w, w.tau, sample_rows=12, heads=[0, 6, 27])
+
+
+# ------------------------------------------------------------------ decode
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 4, 4), ("bf16", 128, 14, 2), ("f32", 64, 4, 2), ("bf16", 64, 3, 1)])
+def test_decode_append_and_attention(dtype, d, Hq, Hkv):
+    say(f"decode dtype={dtype} d={d} Hq={Hq} Hkv={Hkv}")
+    B, cap = 2, 1300
+    G = Hq // Hkv
+    units = B * Hkv
+    w = make_custom(B, Hq, Hkv, cap, d, dtype, seed=31)
+    Kc = dev(w.K, dtype).reshape(units, cap, d).clone()
+    Vc = dev(w.V, dtype).reshape(units, cap, d).clone()
+    lens = [1, 1299, 640, 17][:units] + [5] * max(0, units - 4)
+    ln = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    r = np.random.Generator(np.random.PCG64(32))
+    from workloads import round_to_bf16
+    cast = round_to_bf16 if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    q = cast(r.standard_normal((B * Hq, d)).astype(np.float32) * 2)
+    kn = cast(r.standard_normal((units, d)).astype(np.float32))
+    vn = cast(r.standard_normal((units, d)).astype(np.float32))
+    z.zipvl_kv_append(Kc, Vc, ln, dev(kn, dtype), dev(vn, dtype), B=B, Hkv=Hkv)
+    o = z.zipvl_decode_attn(dev(q, dtype), Kc, Vc, ln, w.scale, B=B, Hq=Hq, Hkv=Hkv)
+    torch.cuda.synchronize()
+    assert ln.cpu().tolist() == [x + 1 for x in lens]
+    oh = host64(o)
+    Kh, Vh = w.K.reshape(units, cap, d), w.V.reshape(units, cap, d)
+    worst = 0.0
+    for b in range(B):
+        for h in range(Hq):
+            u = b * Hkv + h // G
+            ref, Ko, Vo, L1 = oz.decode_step(q[b * Hq + h], kn[u], vn[u], Kh[u], Vh[u], lens[u], w.scale)
+            worst = max(worst, np.abs(oh[b * Hq + h] - ref).max())
+            assert Kc[u, lens[u]].to(torch.float32).cpu().numpy().tobytes() == kn[u].tobytes()
+    say(f"  worst |do| = {worst:.3e}")
+    assert worst <= ATOL_OUT[dtype]

@@ -1,0 +1,111 @@
+"""The C-ABI library without a GPU: it loads, exports what include/zipvl.h
+declares, and rejects bad arguments on the host before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2410_08584_amd as z
+from paper_2410_08584_amd.binding import Dims
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(z.library_path()):
+        from paper_2410_08584_amd.build import build_library
+        build_library(verbose=False)
+    return z.load_library()
+
+
+def _dims(B=1, Hq=4, Hkv=4, n=128, d=64, dtype=0, strides=None):
+    dm = Dims()
+    dm.B, dm.Hq, dm.Hkv, dm.n, dm.d, dm.dtype = B, Hq, Hkv, n, d, dtype
+    s = strides or (Hq * n * d, n * d, d)
+    dm.q_strides = (C.c_int64 * 3)(*s)
+    dm.k_strides = (C.c_int64 * 3)(Hkv * n * d, n * d, d)
+    dm.v_strides = (C.c_int64 * 3)(Hkv * n * d, n * d, d)
+    return dm
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "zipvl.h")).read()
+    declared = set(re.findall(r"\b(zipvl_[a-z_]+)\s*\(", header))
+    assert declared == set(z.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert z.zipvl_version() >= 100
+
+
+def test_workspace_sizes(lib):
+    dm = _dims(B=1, Hq=28, Hkv=4, n=18432, d=128, dtype=1)
+    assert z.workspace_bytes(z.OP_SPARSE_PREFILL, dm) == 2 * 4 * 18432 * 128 * 2
+    assert z.workspace_bytes(z.OP_SELECT, dm) == 0
+    assert z.workspace_bytes(z.OP_SCORE, dm, 64) > 0
+    assert z.workspace_bytes(z.OP_DECODE, dm) > 0
+    assert z.workspace_bytes(99, dm) == 0 and "unknown op" in z.zipvl_last_error()
+
+
+FAKE = C.c_void_p(0x1000)          # aligned, never dereferenced: every call below is rejected first
+
+
+def _score(lib, dm, probes, scale=0.125, Q=FAKE, K=FAKE, mass=FAKE, ws=FAKE, ws_bytes=1 << 30):
+    arr = (C.c_int32 * max(1, len(probes)))(*probes)
+    return lib.zipvl_score(Q, K, C.byref(dm), arr, len(probes), C.c_float(scale), mass, FAKE, ws, ws_bytes, None)
+
+
+def test_score_rejects_bad_arguments(lib):
+    ok = list(range(64, 128))
+    assert _score(lib, _dims(Hq=4, Hkv=3), ok) == -2 and "multiple" in z.zipvl_last_error()
+    assert _score(lib, _dims(d=96), ok) == -2
+    assert _score(lib, _dims(dtype=7), ok) == -5
+    assert _score(lib, _dims(n=0), ok) == -1
+    assert _score(lib, _dims(), ok, Q=None) == -1
+    assert _score(lib, _dims(), ok, Q=C.c_void_p(0x1004)) == -3
+    assert _score(lib, _dims(strides=(4 * 128 * 64, 128 * 64, 66)), ok) == -3
+    assert _score(lib, _dims(), [5, 5, 6]) == -1 and "ascending" in z.zipvl_last_error()
+    assert _score(lib, _dims(), [5, 128]) == -1
+    assert _score(lib, _dims(), []) == -1
+    assert _score(lib, _dims(), list(range(65))) == -2
+    assert _score(lib, _dims(), ok, scale=0.0) == -1
+    assert _score(lib, _dims(), ok, ws=None) == -4
+    assert _score(lib, _dims(), ok, ws_bytes=16) == -4 and "workspace" in z.zipvl_last_error()
+
+
+def test_select_rejects_bad_arguments(lib):
+    f = lib.zipvl_select
+    assert f(None, None, 1, 8, C.c_double(0.9), FAKE, FAKE, None, 0, None) == -1
+    assert f(FAKE, None, 0, 8, C.c_double(0.9), FAKE, FAKE, None, 0, None) == -1
+    assert f(FAKE, None, 1, 8, C.c_double(0.0), FAKE, FAKE, None, 0, None) == -1
+    assert f(FAKE, None, 1, 8, C.c_double(1.5), FAKE, FAKE, None, 0, None) == -1
+    assert f(FAKE, None, 1, 8, C.c_double(float("nan")), FAKE, FAKE, None, 0, None) == -1
+    assert f(C.c_void_p(0x1002), None, 1, 8, C.c_double(0.9), FAKE, FAKE, None, 0, None) == -3
+
+
+def test_prefill_compact_decode_reject_bad_arguments(lib):
+    dm = _dims()
+    sp = lib.zipvl_sparse_prefill
+    assert sp(FAKE, FAKE, FAKE, C.byref(dm), FAKE, None, C.c_float(0.1), 0, FAKE, FAKE, 1 << 30, None) == -1
+    assert sp(FAKE, FAKE, FAKE, C.byref(dm), None, None, C.c_float(0.1), 8, FAKE, FAKE, 1 << 30, None) == -5
+    assert sp(FAKE, FAKE, FAKE, C.byref(dm), None, None, C.c_float(0.1), 0, FAKE, FAKE, 8, None) == -4
+    assert sp(FAKE, FAKE, FAKE, C.byref(dm), None, None, C.c_float(0.1), 0, FAKE, C.c_void_p(0x1010), 1 << 30, None) == -3
+    ck = lib.zipvl_compact_kv
+    assert ck(FAKE, FAKE, C.byref(dm), None, None, FAKE, FAKE, 0, FAKE, None) == -1
+    assert ck(FAKE, FAKE, C.byref(dm), FAKE, None, FAKE, FAKE, 16, FAKE, None) == -1
+    assert ck(FAKE, FAKE, C.byref(dm), None, None, FAKE, FAKE, 16, None, None) == -1
+    dc = lib.zipvl_decode_attn
+    assert dc(FAKE, FAKE, FAKE, None, 16, C.byref(dm), C.c_float(0.1), FAKE, FAKE, 1 << 30, None) == -1
+    assert dc(FAKE, FAKE, FAKE, FAKE, 16, C.byref(dm), C.c_float(0.1), FAKE, FAKE, 4, None) == -4
+    ap = lib.zipvl_kv_append
+    assert ap(FAKE, FAKE, None, 16, FAKE, FAKE, C.byref(dm), None) == -1
+    assert ap(FAKE, FAKE, FAKE, 0, FAKE, FAKE, C.byref(dm), None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_2410_08584_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_NAME", "libzipvl_not_built.so")
+    with pytest.raises(z.ZipvlError):
+        b.load_library()
