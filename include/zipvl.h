@@ -158,6 +158,28 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
                       int32_t cap, const zipvl_dims* dims, float softmax_scale,
                       void* o, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the method).  While enabled,
+ * every kernel launch of the calling process is bracketed by two HIP events on
+ * its own stream (up to 8192 launches are kept; later ones are not timed).
+ * zipvl_timing_read waits for the recorded events and returns the summed
+ * duration and launch count of one kernel, then keeps accumulating;
+ * zipvl_timing_enable(1) clears the records, zipvl_timing_enable(0) stops.
+ */
+#define ZIPVL_K_SCORE_ROWSTATS  0
+#define ZIPVL_K_SCORE_COLSUM    1
+#define ZIPVL_K_SELECT          2
+#define ZIPVL_K_COMPACT_KV      3
+#define ZIPVL_K_KV_APPEND       4
+#define ZIPVL_K_ZERO_FILL       5
+#define ZIPVL_K_PACK_KV         6
+#define ZIPVL_K_FLASH_KEPT      7
+#define ZIPVL_K_DECODE_PARTIAL  8
+#define ZIPVL_K_DECODE_COMBINE  9
+#define ZIPVL_K_COUNT          10
+int zipvl_timing_enable(int on);
+int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
+
 #ifdef __cplusplus
 }
 #endif

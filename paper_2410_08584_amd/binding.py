@@ -15,7 +15,8 @@ OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT = 0, 1, 2
 OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE = 1, 2, 3, 4
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
-           "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn")
+           "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
+           "zipvl_timing_enable", "zipvl_timing_read")
 
 
 class ZipvlError(RuntimeError):
@@ -61,6 +62,10 @@ def load_library():
     lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
     lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
                                       C.c_size_t, vp]
+    lib.zipvl_timing_enable.argtypes = [C.c_int]
+    lib.zipvl_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
+    lib.zipvl_timing_enable.restype = C.c_int
+    lib.zipvl_timing_read.restype = C.c_int
     for name in ("zipvl_score", "zipvl_select", "zipvl_sparse_prefill", "zipvl_compact_kv",
                  "zipvl_kv_append", "zipvl_decode_attn"):
         getattr(lib, name).restype = C.c_int
@@ -220,3 +225,18 @@ def zipvl_decode_attn(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lengt
     _check(lib.zipvl_decode_attn(_ptr(q), _ptr(Kc), _ptr(Vc), _ptr(length), int(cap), C.byref(dm),
                                  float(softmax_scale), _ptr(o), _ptr(ws), ws.numel(), _stream()))
     return o
+
+
+KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
+           "pack_kv", "flash_kept", "decode_partial", "decode_combine")
+
+
+def zipvl_timing_enable(on: bool) -> None:
+    _check(load_library().zipvl_timing_enable(1 if on else 0))
+
+
+def zipvl_timing_read(kernel: int):
+    """(total milliseconds, launches) of one kernel since timing was enabled."""
+    ms, cnt = C.c_double(0.0), C.c_int(0)
+    _check(load_library().zipvl_timing_read(int(kernel), C.byref(ms), C.byref(cnt)))
+    return ms.value, cnt.value

@@ -295,13 +295,17 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     if (!out_compact && idx) {
         const int64_t n16 = (int64_t)d.B * d.Hq * d.n * D * C::E / 16;
         const int blocks = (int)(n16 / 256 / 4 < 1 ? 1 : (n16 / 256 / 4 > 8192 ? 8192 : n16 / 256 / 4));
+        KernelTimer tm(ZIPVL_K_ZERO_FILL, st);
         hipLaunchKernelGGL((zero_fill_kernel<T>), dim3(blocks), dim3(256), 0, st, (uintx4*)O, n16);
         int rc = check_launch("zero_fill");
         if (rc) return rc;
     }
-    hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kBN, units), dim3(256), 0, st,
-        (const T*)K, (const T*)V, d.k_strides[0], d.k_strides[1], d.k_strides[2],
-        d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept);
+    {
+        KernelTimer tm(ZIPVL_K_PACK_KV, st);
+        hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kBN, units), dim3(256), 0, st,
+            (const T*)K, (const T*)V, d.k_strides[0], d.k_strides[1], d.k_strides[2],
+            d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept);
+    }
     int rc = check_launch("pack_kv");
     if (rc) return rc;
 
@@ -312,9 +316,12 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
             return set_error(ZIPVL_EHIP, "sparse_prefill: cannot reserve %d bytes of LDS", C::LDS_BYTES);
         attr_done = true;
     }
-    hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((d.n + kBM - 1) / kBM, d.B * d.Hq), dim3(256),
-        C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-        (const T*)Kp, (const T*)VTp, idx, k, (T*)O, d.n, npad, d.Hq, d.Hkv, scale * kLog2e, out_compact);
+    {
+        KernelTimer tm(ZIPVL_K_FLASH_KEPT, st);
+        hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((d.n + kBM - 1) / kBM, d.B * d.Hq), dim3(256),
+            C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
+            (const T*)Kp, (const T*)VTp, idx, k, (T*)O, d.n, npad, d.Hq, d.Hkv, scale * kLog2e, out_compact);
+    }
     return check_launch("flash_kept");
 }
 

@@ -60,6 +60,7 @@ int launch_compact_kv(const void* K, const void* V, const zipvl_dims& d, const i
     const int e = d.dtype == ZIPVL_BF16 ? 2 : 4;
     const int units = d.B * d.Hkv;
     dim3 grid((min(d.n, cap) + kCompactRows - 1) / kCompactRows, units);
+    KernelTimer tm(ZIPVL_K_COMPACT_KV, st);
     hipLaunchKernelGGL(compact_kv_kernel, grid, dim3(256), 0, st,
         (const char*)K, (const char*)V,
         d.k_strides[0] * e, d.k_strides[1] * e, d.k_strides[2] * e,
@@ -72,6 +73,7 @@ int launch_kv_append(void* Kc, void* Vc, int32_t* len, int32_t cap, const void* 
                      const void* v_new, const zipvl_dims& d, hipStream_t st)
 {
     const int e = d.dtype == ZIPVL_BF16 ? 2 : 4;
+    KernelTimer tm(ZIPVL_K_KV_APPEND, st);
     hipLaunchKernelGGL(kv_append_kernel, dim3(d.B * d.Hkv), dim3(64), 0, st,
         (char*)Kc, (char*)Vc, len, cap, (const char*)k_new, (const char*)v_new, d.d * e);
     return check_launch("kv_append");

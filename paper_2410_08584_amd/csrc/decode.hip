@@ -207,6 +207,7 @@ static int launch_decode_t(const void* q, const void* Kc, const void* Vc, const 
         (const T*)Kc, (const T*)Vc, len, cap, d.Hq, d.Hkv, GB, c, (float*)ws, nsplit)
     for (int gb = 0; gb < G; gb += 8) {
         const int rem = G - gb;
+        KernelTimer tm(ZIPVL_K_DECODE_PARTIAL, st);
         if (rem >= 5) ZIPVL_DEC(8, gb);
         else if (rem >= 3) ZIPVL_DEC(4, gb);
         else if (rem == 2) ZIPVL_DEC(2, gb);
@@ -215,6 +216,7 @@ static int launch_decode_t(const void* q, const void* Kc, const void* Vc, const 
         if (rc) return rc;
     }
 #undef ZIPVL_DEC
+    KernelTimer tm(ZIPVL_K_DECODE_COMBINE, st);
     hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(d.B * d.Hq), dim3(D), 0, st,
         (const float*)ws, nsplit, (T*)o);
     return check_launch("decode_combine");

@@ -4,6 +4,14 @@
 
 namespace zipvl {
 
+// Optional per-kernel timing with HIP events on the launch stream (off by default).
+struct KernelTimer {
+    KernelTimer(int kernel_id, hipStream_t st);
+    ~KernelTimer();
+    int slot;
+    hipStream_t st;
+};
+
 struct ProbeList {            // passed by value in the kernel arguments
     int32_t pos[ZIPVL_MAX_PROBES];
 };

@@ -242,10 +242,13 @@ static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, con
 {
     const float c = scale * kLog2e;
     float2* partial = (float2*)ws;
-    hipLaunchKernelGGL((score_rowstats_kernel<T, D>), dim3(p.nsplit, d.B * d.Hq), dim3(256), 0, st,
-        (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-        d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, p.n_eff, c, partial,
-        p.nsplit, p.keys_per_split, d.Hq, d.Hkv);
+    {
+        KernelTimer tm(ZIPVL_K_SCORE_ROWSTATS, st);
+        hipLaunchKernelGGL((score_rowstats_kernel<T, D>), dim3(p.nsplit, d.B * d.Hq), dim3(256), 0, st,
+            (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
+            d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, p.n_eff, c, partial,
+            p.nsplit, p.keys_per_split, d.Hq, d.Hkv);
+    }
     int rc = check_launch("score_rowstats");
     if (rc) return rc;
 #define ZIPVL_COLSUM(KBV)                                                                          \
@@ -254,6 +257,7 @@ static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, con
         (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],                  \
         d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, p.n_eff, c,                    \
         (const float2*)partial, p.nsplit, mass, rank, d.Hq, d.Hkv)
+    KernelTimer tm(ZIPVL_K_SCORE_COLSUM, st);
     if (p.KB == 4) ZIPVL_COLSUM(4);
     else if (p.KB == 2) ZIPVL_COLSUM(2);
     else ZIPVL_COLSUM(1);

@@ -239,6 +239,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 int launch_select(const float* mass, const float* rank, int units, int n, double tau,
                   int32_t* idx, int32_t* k, hipStream_t st)
 {
+    KernelTimer tm(ZIPVL_K_SELECT, st);
     hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, st, mass, rank, n, tau, idx, k);
     return check_launch("select");
 }

@@ -3,6 +3,8 @@
 // nothing.
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
+#include <vector>
 #include "launch.h"
 
 namespace zipvl {
@@ -21,6 +23,39 @@ int check_launch(const char* what) {
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return set_error(ZIPVL_EHIP, "%s: launch failed: %s", what, hipGetErrorString(e));
     return ZIPVL_OK;
+}
+
+// ---- optional kernel timing -------------------------------------------------
+namespace {
+constexpr int kMaxTimed = 8192;
+struct TimedLaunch { int id; hipEvent_t start, stop; };
+std::mutex g_tmu;
+bool g_timing = false;
+std::vector<TimedLaunch> g_timed;
+std::vector<hipEvent_t> g_pool;       // created once, reused
+int g_pool_used = 0;
+}  // namespace
+
+KernelTimer::KernelTimer(int kernel_id, hipStream_t s) : slot(-1), st(s) {
+    if (!g_timing) return;
+    std::lock_guard<std::mutex> lk(g_tmu);
+    if ((int)g_timed.size() >= kMaxTimed) return;
+    while ((int)g_pool.size() < g_pool_used + 2) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        g_pool.push_back(e);
+    }
+    TimedLaunch t{kernel_id, g_pool[g_pool_used], g_pool[g_pool_used + 1]};
+    g_pool_used += 2;
+    if (hipEventRecord(t.start, st) != hipSuccess) return;
+    slot = (int)g_timed.size();
+    g_timed.push_back(t);
+}
+
+KernelTimer::~KernelTimer() {
+    if (slot < 0) return;
+    std::lock_guard<std::mutex> lk(g_tmu);
+    (void)hipEventRecord(g_timed[slot].stop, st);
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -187,6 +222,33 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
     if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
     if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
     return launch_decode_attn(q, Kc, Vc, len, cap, *dims, softmax_scale, o, ws, (hipStream_t)stream);
+}
+
+int zipvl_timing_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_tmu);
+    g_timed.clear();
+    g_pool_used = 0;
+    g_timing = on != 0;
+    return ZIPVL_OK;
+}
+
+int zipvl_timing_read(int kernel_id, double* total_ms, int* launches) {
+    if (!total_ms || !launches) return set_error(ZIPVL_EINVAL, "zipvl_timing_read: NULL output");
+    if (kernel_id < 0 || kernel_id >= ZIPVL_K_COUNT) return set_error(ZIPVL_EINVAL, "zipvl_timing_read: kernel id %d", kernel_id);
+    std::lock_guard<std::mutex> lk(g_tmu);
+    double sum = 0.0;
+    int cnt = 0;
+    for (const TimedLaunch& t : g_timed) {
+        if (t.id != kernel_id) continue;
+        if (hipEventSynchronize(t.stop) != hipSuccess) return set_error(ZIPVL_EHIP, "zipvl_timing_read: event wait failed");
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess) return set_error(ZIPVL_EHIP, "zipvl_timing_read: elapsed time failed");
+        sum += ms;
+        ++cnt;
+    }
+    *total_ms = sum;
+    *launches = cnt;
+    return ZIPVL_OK;
 }
 
 }  // extern "C"
