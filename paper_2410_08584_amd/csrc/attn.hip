@@ -39,6 +39,7 @@ struct AttnCfg {
     static constexpr int K_TILE = kBN * KS;
     static constexpr int V_TILE = D * VS;
     static constexpr int LDS_BYTES = 2 * (K_TILE + V_TILE);
+    static constexpr int MIN_WAVES = (E == 2) ? 2 : 1;       // bf16: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs)
 };
 
 // ------------------------------------------------------------------ pack
@@ -167,7 +168,7 @@ template <> __device__ __forceinline__ void store_out4<__bf16>(__bf16* dst, floa
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void flash_kept_kernel(
+__global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_kernel(
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
     const T* __restrict__ Kp, const T* __restrict__ VTp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
@@ -220,7 +221,6 @@ __global__ __launch_bounds__(256) void flash_kept_kernel(
         // S^T block blk: keys t0 + 32*blk + acc_row(r, h), query column = this lane's
         float p[2][16];
         float mx = -INFINITY;
-        const bool need_mask = t0 + kBN - 1 > wave_first_row;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
             floatx16 acc = {0};
@@ -230,30 +230,41 @@ __global__ __launch_bounds__(256) void flash_kept_kernel(
                 acc = mma_frag<T>(a, qf[cc], acc);
             }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float s = acc[r] * c;
-                if (need_mask && t0 + 32 * blk + acc_row(r, h) > qrow) s = -INFINITY;
-                p[blk][r] = s;
-                mx = fmaxf(mx, s);
-            }
+            for (int r = 0; r < 16; ++r) p[blk][r] = acc[r];
         }
+        if (t0 + kBN - 1 > wave_first_row) {                 // tile touches the diagonal (wave-uniform)
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (t0 + 32 * blk + acc_row(r, h) > qrow) p[blk][r] = -INFINITY;
+        }
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, p[blk][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
+        // raw-logit maximum; the softmax scale (c > 0, log2 domain) is folded into the exponent
         const float m_new = fmaxf(m_run, mx);                // finite: key 0 is visible to every row
-        const float alpha = fast_exp2(m_run - m_new);
+        const float mc = m_new * c;
         float sum = 0.f;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                p[blk][r] = fast_exp2(p[blk][r] - m_new);
+                p[blk][r] = fast_exp2(fmaf(p[blk][r], c, -mc));
                 sum += p[blk][r];
             }
-        l_run = l_run * alpha + sum;
-        m_run = m_new;
+        if (__any(m_new != m_run)) {                         // rescale only when some row's maximum moved
+            const float alpha = fast_exp2(m_run * c - mc);
+            l_run *= alpha;
 #pragma unroll
-        for (int db = 0; db < C::ODB; ++db)
+            for (int db = 0; db < C::ODB; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+            m_run = m_new;
+        }
+        l_run += sum;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) PV<T, D>::run(vs, i, h, blk, p[blk], o);
     }
