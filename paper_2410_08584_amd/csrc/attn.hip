@@ -39,10 +39,21 @@ struct AttnCfg {
     static constexpr int K_TILE = kBN * KS;
     static constexpr int V_TILE = D * VS;
     static constexpr int LDS_BYTES = 2 * (K_TILE + V_TILE);
+    static constexpr int NVF = (E == 2 ? 2 : 4) * ODB;       // V^T operand fragments per 32 keys per lane
     static constexpr int MIN_WAVES = (E == 2) ? 2 : 1;       // bf16: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs)
 };
 
 // ------------------------------------------------------------------ pack
+// Key held at element e of 16-byte chunk kc of a V^T tile row.  fp32: natural order.  bf16: inside
+// every group of 16 keys the order is [0..3, 8..11 | 4..7, 12..15], which is the order in which the
+// two half-waves hold the 8 contraction slots of one P^T fragment, so that a lane's V^T operand is
+// one contiguous 16-byte read.
+template <typename T> __device__ __forceinline__ int vt_key(int kc, int e);
+template <> __device__ __forceinline__ int vt_key<float>(int kc, int e) { return kc * 4 + e; }
+template <> __device__ __forceinline__ int vt_key<__bf16>(int kc, int e) {
+    return 16 * (kc >> 1) + 8 * (e >> 2) + 4 * (kc & 1) + (e & 3);
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void pack_kv_kernel(
     const T* __restrict__ K, const T* __restrict__ V,
@@ -78,7 +89,7 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
         const int dd = wi % D, kc = wi / D;
         T v[EPF];
 #pragma unroll
-        for (int e = 0; e < EPF; ++e) v[e] = tile[(kc * EPF + e) * LS + dd];
+        for (int e = 0; e < EPF; ++e) v[e] = tile[vt_key<T>(kc, e) * LS + dd];
         store16(VT + dd * kBN + kc * EPF, *reinterpret_cast<const uintx4*>(v));
     }
 }
@@ -112,50 +123,60 @@ __device__ __forceinline__ void stage_tile(char* ks, char* vs, int tid,
     }
 }
 
-// P^T (32 keys x 32 queries block `blk`, registers p[16]) times V^T tile -> O^T accumulators.
+// P^T (64 keys x 32 queries, registers p[2][16]) times the V^T tile -> O^T accumulators, in two
+// halves of 32 keys (HALF = S^T block).  `load` fetches the V^T operand fragments of one half from
+// LDS, `run` consumes them.
 template <typename T, int D> struct PV;
 
 template <int D> struct PV<__bf16, D> {
-    __device__ static __forceinline__ void run(const char* vs, int i, int h, int blk, const float (&p)[16],
-                                               floatx16 (&o)[AttnCfg<__bf16, D>::ODB]) {
-        using C = AttnCfg<__bf16, D>;
+    using C = AttnCfg<__bf16, D>;
+    // fragment (s2, db): 16-key step s = 2*HALF + s2, 32-row block db of O^T
+    template <int HALF>
+    __device__ static __forceinline__ void load(const char* vs, int i, int h, uintx4 (&vf)[C::NVF]) {
 #pragma unroll
-        for (int a2 = 0; a2 < 2; ++a2) {
-            // contraction slot t of this lane <-> key 32*blk + 16*a2 + 8*(t/4) + 4*h + t%4
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int db = 0; db < C::ODB; ++db)     // V^T rows are stored in contraction-slot order
+                vf[s2 * C::ODB + db] = *reinterpret_cast<const uintx4*>(
+                    vs + (db * 32 + i) * C::VS + (2 * HALF + s2) * 32 + h * 16);
+    }
+    __device__ static __forceinline__ void run(const uintx4 (&vf)[C::NVF], const float (&p)[16], floatx16 (&o)[C::ODB]) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            // contraction slot t of this lane <-> key 16*s2 + 8*(t/4) + 4*h + t%4 of the half = register 8*s2 + t
             uintx4 bfrag;
-            bfrag[0] = pack_bf16x2(p[8 * a2 + 0], p[8 * a2 + 1]);
-            bfrag[1] = pack_bf16x2(p[8 * a2 + 2], p[8 * a2 + 3]);
-            bfrag[2] = pack_bf16x2(p[8 * a2 + 4], p[8 * a2 + 5]);
-            bfrag[3] = pack_bf16x2(p[8 * a2 + 6], p[8 * a2 + 7]);
-            const int koff = (32 * blk + 16 * a2 + 4 * h) * 2;
+            bfrag[0] = pack_bf16x2(p[8 * s2 + 0], p[8 * s2 + 1]);
+            bfrag[1] = pack_bf16x2(p[8 * s2 + 2], p[8 * s2 + 3]);
+            bfrag[2] = pack_bf16x2(p[8 * s2 + 4], p[8 * s2 + 5]);
+            bfrag[3] = pack_bf16x2(p[8 * s2 + 6], p[8 * s2 + 7]);
 #pragma unroll
-            for (int db = 0; db < C::ODB; ++db) {
-                const char* row = vs + (db * 32 + i) * C::VS + koff;
-                const uintx2 lo = *reinterpret_cast<const uintx2*>(row);
-                const uintx2 hi = *reinterpret_cast<const uintx2*>(row + 16);
-                const uintx4 afrag = {lo[0], lo[1], hi[0], hi[1]};
-                o[db] = mma_frag<__bf16>(afrag, bfrag, o[db]);
-            }
+            for (int db = 0; db < C::ODB; ++db) o[db] = mma_frag<__bf16>(vf[s2 * C::ODB + db], bfrag, o[db]);
         }
     }
 };
 
 template <int D> struct PV<float, D> {
-    __device__ static __forceinline__ void run(const char* vs, int i, int h, int blk, const float (&p)[16],
-                                               floatx16 (&o)[AttnCfg<float, D>::ODB]) {
-        using C = AttnCfg<float, D>;
+    using C = AttnCfg<float, D>;
+    // fragment (a, db): keys 32*HALF + 8*a + 4*h + t (t = 0..3) of O^T block db
+    template <int HALF>
+    __device__ static __forceinline__ void load(const char* vs, int i, int h, uintx4 (&vf)[C::NVF]) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            // step (a, t): this lane contributes key 32*blk + 8*a + 4*h + t
-            const int koff = (32 * blk + 8 * a + 4 * h) * 4;
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int db = 0; db < C::ODB; ++db)
+                vf[a * C::ODB + db] = *reinterpret_cast<const uintx4*>(
+                    vs + (db * 32 + i) * C::VS + (32 * HALF + 8 * a + 4 * h) * 4);
+    }
+    __device__ static __forceinline__ void run(const uintx4 (&vf)[C::NVF], const float (&p)[16], floatx16 (&o)[C::ODB]) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
             for (int db = 0; db < C::ODB; ++db) {
-                const floatx4 v = *reinterpret_cast<const floatx4*>(vs + (db * 32 + i) * C::VS + koff);
+                const floatx4 v = __builtin_bit_cast(floatx4, vf[a * C::ODB + db]);
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(v[t], p[4 * a + t], o[db], 0, 0, 0);
             }
-        }
     }
 };
 
@@ -221,17 +242,29 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
         // S^T block blk: keys t0 + 32*blk + acc_row(r, h), query column = this lane's
         float p[2][16];
         float mx = -INFINITY;
+        {
+            // all K fragments of the tile are requested before the first matrix op, so that the LDS
+            // latency is paid once per tile and not once per fragment
+            uintx4 kf[2][C::CH];
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk) {
-            floatx16 acc = {0};
+            for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-            for (int cc = 0; cc < C::CH; ++cc) {
-                const uintx4 a = *reinterpret_cast<const uintx4*>(ks + (blk * 32 + i) * C::KS + cc * 32 + h * 16);
-                acc = mma_frag<T>(a, qf[cc], acc);
+                for (int cc = 0; cc < C::CH; ++cc)
+                    kf[blk][cc] = *reinterpret_cast<const uintx4*>(ks + (blk * 32 + i) * C::KS + cc * 32 + h * 16);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+                floatx16 acc = {0};
+#pragma unroll
+                for (int cc = 0; cc < C::CH; ++cc) acc = mma_frag<T>(kf[blk][cc], qf[cc], acc);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) p[blk][r] = acc[r];
             }
-#pragma unroll
-            for (int r = 0; r < 16; ++r) p[blk][r] = acc[r];
         }
+        // the first half of the V^T fragments is requested now and lands while the softmax runs
+        uintx4 vf0[C::NVF], vf1[C::NVF];
+        PV<T, D>::template load<0>(vs, i, h, vf0);
+        __builtin_amdgcn_sched_barrier(0);
         if (t0 + kBN - 1 > wave_first_row) {                 // tile touches the diagonal (wave-uniform)
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk)
@@ -265,8 +298,10 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
             m_run = m_new;
         }
         l_run += sum;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk) PV<T, D>::run(vs, i, h, blk, p[blk], o);
+        __builtin_amdgcn_sched_barrier(0);
+        PV<T, D>::template load<1>(vs, i, h, vf1);           // lands under the matrix ops of the first half
+        PV<T, D>::run(vf0, p[0], o);
+        PV<T, D>::run(vf1, p[1], o);
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
