@@ -99,7 +99,8 @@ int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims,
  * sorted accumulated scores reach tau of the total) and Eq. (9) (that many
  * tokens with the largest normalised score); Algorithm 1, steps 3-5.
  *
- * Per unit u (row u of mass/rank, n entries each, finite and >= 0, sum < 4096):
+ * Per unit u (row u of mass/rank, n entries each, finite and >= 0, sum < 4096; an entry with the
+ * sign bit set is ordered and summed as 0):
  *   q_j = floor(mass_j * 2^40)  (exact integers; the sums below are integer sums)
  *   k   = n if tau >= 1, else max(1, min{ i : sum of the i largest q >= ceil(tau * sum of all q) })
  *   T   = the k tokens with the largest rank (equal values: lower index first)
@@ -176,7 +177,8 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
 #define ZIPVL_K_FLASH_KEPT      7
 #define ZIPVL_K_DECODE_PARTIAL  8
 #define ZIPVL_K_DECODE_COMBINE  9
-#define ZIPVL_K_COUNT          10
+#define ZIPVL_K_SCORE_ROWFINAL 10
+#define ZIPVL_K_COUNT          11
 int zipvl_timing_enable(int on);
 int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
 

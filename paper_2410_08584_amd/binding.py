@@ -228,7 +228,7 @@ def zipvl_decode_attn(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lengt
 
 
 KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
-           "pack_kv", "flash_kept", "decode_partial", "decode_combine")
+           "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal")
 
 
 def zipvl_timing_enable(on: bool) -> None:

@@ -14,8 +14,9 @@
 //          per-lane scalars and only the running maximum crosses lanes (one
 //          exchange between the two half-waves per tile).  Causality is the
 //          plain lower triangle in kept-token coordinates because T is
-//          ascending.  Query rows are gathered by idx on load and output rows
-//          are scattered by idx on store.
+//          ascending.  Query rows are gathered by idx on load, output rows are
+//          scattered by idx on store, and the rows of dropped tokens between a
+//          workgroup's kept rows are cleared by that workgroup (no separate fill).
 // The kept count k lives on the device: the grid covers the worst case (k = n)
 // and workgroups beyond a unit's k exit at once; heavy (late) query tiles are
 // scheduled first.
@@ -92,12 +93,6 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
         for (int e = 0; e < EPF; ++e) v[e] = tile[vt_key<T>(kc, e) * LS + dd];
         store16(VT + dd * kBN + kc * EPF, *reinterpret_cast<const uintx4*>(v));
     }
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void zero_fill_kernel(uintx4* __restrict__ p, int64_t n16) {
-    const uintx4 z = {0, 0, 0, 0};
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) p[i] = z;
 }
 
 // ------------------------------------------------------------------ flash
@@ -180,6 +175,16 @@ template <int D> struct PV<float, D> {
     }
 };
 
+// rows [lo, hi) of head bh of O := 0, spread over `nthreads` threads (16-byte stores)
+template <typename T, int D>
+__device__ __forceinline__ void zero_rows(T* O, int bh, int n, int lo, int hi, int tid, int nthreads) {
+    constexpr int CPR = D * Elem<T>::kBytes / 16;
+    const uintx4 z = {0, 0, 0, 0};
+    char* base = reinterpret_cast<char*>(O + ((int64_t)bh * n + lo) * D);
+    const int64_t chunks = (int64_t)(hi - lo) * CPR;
+    for (int64_t q = tid; q < chunks; q += nthreads) store16(base + q * 16, z);
+}
+
 template <typename T> __device__ __forceinline__ void store_out4(T* dst, float a, float b, float c, float d);
 template <> __device__ __forceinline__ void store_out4<float>(float* dst, float a, float b, float c, float d) {
     *reinterpret_cast<floatx4*>(dst) = floatx4{a, b, c, d};
@@ -193,19 +198,45 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
     const T* __restrict__ Kp, const T* __restrict__ VTp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
-    T* __restrict__ O, int n, int npad, int Hq, int Hkv, float c, int out_compact)
+    T* __restrict__ O, int n, int npad, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped)
 {
     using C = AttnCfg<T, D>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int tile_q = gridDim.x - 1 - blockIdx.x;          // heavy tiles first
+    // heads vary fastest and heavy (late) query tiles come first: all heads' longest tiles are
+    // dispatched before any short one, and neighbouring workgroups share a KV head's tiles in L2
+    const int bh = blockIdx.x % BH, b = bh / Hq, head = bh - b * Hq;
+    const int tile_q = (int)(gridDim.x / BH) - 1 - (int)(blockIdx.x / BH);
     const int i0 = tile_q * kBM;
-    const int bh = blockIdx.y, b = bh / Hq, head = bh - b * Hq;
     const int G = Hq / Hkv, g = head / G, u = b * Hkv + g;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
     int kk = kcnt ? kcnt[u] : n;
     kk = max(0, min(kk, n));
-    if (i0 >= kk) return;
-
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
+    if (i0 >= kk) {
+        if (zero_dropped && i0 == 0) zero_rows<T, D>(O, bh, n, 0, n, tid, 256);   // nothing kept at all
+        return;
+    }
+    if (zero_dropped) {
+        // Outputs of dropped tokens are zero rows.  This workgroup clears the dropped positions that
+        // lie before each of its kept rows; the tile holding the last kept row also clears the tail.
+        int* tpos = reinterpret_cast<int*>(smem);            // [kBM + 1], dead before the first tile is staged
+        if (tid <= kBM) {
+            const int r = i0 - 1 + tid;                      // entry e: position of kept row i0 - 1 + e
+            tpos[tid] = r < 0 ? -1 : (r < kk ? idx[(int64_t)u * n + r] : n);
+        }
+        __syncthreads();
+        if (i0 + kBM == kk) zero_rows<T, D>(O, bh, n, tpos[kBM] + 1, n, tid, 256);   // tail after a full last tile
+#pragma unroll
+        for (int half = 0; half < kBM / 64; ++half) {
+            const int gi = half * 64 + lane;
+            unsigned long long open = __ballot(tpos[gi + 1] - tpos[gi] > 1);
+            while (open) {                                   // wave-uniform walk over the non-empty gaps
+                const int gsel = half * 64 + __builtin_ctzll(open);
+                open &= open - 1;
+                zero_rows<T, D>(O, bh, n, tpos[gsel] + 1, tpos[gsel + 1], tid, 256);
+            }
+        }
+        __syncthreads();                                     // tpos is overwritten by the first K tile
+    }
     const int qrow = i0 + 32 * w + i;                        // kept-token coordinate of this lane's query
     const int qclamp = min(qrow, kk - 1);
     const int qpos = idx ? idx[(int64_t)u * n + qclamp] : qclamp;
@@ -338,14 +369,6 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     const int out_compact = (flags & ZIPVL_OUT_COMPACT) ? 1 : 0;
     const int rows_are_kept = (flags & ZIPVL_KV_ALREADY_COMPACT) ? 1 : 0;
 
-    if (!out_compact && idx) {
-        const int64_t n16 = (int64_t)d.B * d.Hq * d.n * D * C::E / 16;
-        const int blocks = (int)(n16 / 256 / 4 < 1 ? 1 : (n16 / 256 / 4 > 8192 ? 8192 : n16 / 256 / 4));
-        KernelTimer tm(ZIPVL_K_ZERO_FILL, st);
-        hipLaunchKernelGGL((zero_fill_kernel<T>), dim3(blocks), dim3(256), 0, st, (uintx4*)O, n16);
-        int rc = check_launch("zero_fill");
-        if (rc) return rc;
-    }
     {
         KernelTimer tm(ZIPVL_K_PACK_KV, st);
         hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kBN, units), dim3(256), 0, st,
@@ -364,9 +387,13 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     }
     {
         KernelTimer tm(ZIPVL_K_FLASH_KEPT, st);
-        hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((d.n + kBM - 1) / kBM, d.B * d.Hq), dim3(256),
+        const int BH = d.B * d.Hq;
+        const int64_t blocks = (int64_t)((d.n + kBM - 1) / kBM) * BH;
+        if (blocks > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
+        hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((unsigned)blocks), dim3(256),
             C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-            (const T*)Kp, (const T*)VTp, idx, k, (T*)O, d.n, npad, d.Hq, d.Hkv, scale * kLog2e, out_compact);
+            (const T*)Kp, (const T*)VTp, idx, k, (T*)O, d.n, npad, BH, d.Hq, d.Hkv, scale * kLog2e,
+            out_compact, (!out_compact && idx) ? 1 : 0);
     }
     return check_launch("flash_kept");
 }

@@ -1,28 +1,38 @@
 // Probe-token importance scores (supplementary Eq. (A); Eq. (6), Eq. (8);
 // Algorithm 1 steps 2-4).  The m x n probe attention matrix is never stored:
-//   pass 1  row statistics: for each (head, probe row) the running maximum
-//           and exp-sum of the masked, scaled logits over a slice of keys,
-//           one partial per key slice;
-//   pass 2  the logits are recomputed tile by tile, normalised with the merged
-//           row statistics, summed down the probe rows and over the query
-//           heads of the group, and written as mass / rank.
-// Both passes take the logits on the matrix cores: a 32-key x 32-probe tile is
-// one 32x32 MFMA accumulator, operands are read straight from global memory as
-// 16-byte fragments (K rows are consumed whole by consecutive fragments).
-// Pass 1 computes K Q^T (lane = probe column, so row statistics stay in the
-// lane); pass 2 computes Q K^T (lane = key column, so column sums stay in the
-// lane).  Same registers, operands swapped.
+//   pass 1  row statistics: for each (head, probe row) the maximum and the
+//           exp-sum of the masked, scaled logits over a slice of 128 keys;
+//           a small kernel merges the slices into one exponent offset per row;
+//   pass 2  the logits are recomputed, normalised with that offset, summed
+//           down the probe rows and over the query heads of the group, and
+//           written as mass / rank.
+// Both passes share one kernel body.  A workgroup (4 waves) owns 128 keys of
+// one KV head: each wave keeps the fragments of its 32 keys in registers and
+// walks over the group's query heads, whose probe rows pass through LDS a few
+// heads at a time (small footprint, several workgroups per CU), so K is read
+// from memory once per pass.  A 32-key x 32-probe tile is one 32x32 MFMA
+// accumulator.  Pass 1 computes K Q^T (lane = probe column: row statistics
+// stay in the lane); pass 2 computes Q K^T (lane = key column: column sums
+// stay in the lane).  Same fragments, operands swapped.
 #include "launch.h"
 
 namespace zipvl {
 
 constexpr int kNB = ZIPVL_MAX_PROBES / 32;   // probe blocks of 32 (rows beyond m are masked out)
-constexpr int kMaxSplit = 32;
+constexpr int kProbes = kNB * 32;
 constexpr int kMaxGroup = 16;
+constexpr int kScoreWaves = 4;
+constexpr int kScoreThreads = 64 * kScoreWaves;
+constexpr int kScoreKeys = 32 * kScoreWaves;  // keys per workgroup
 
 template <typename T, int D>
 struct ScoreCfg {
+    static constexpr int E = Elem<T>::kBytes;
     static constexpr int CH = D / Elem<T>::kPerChunk;      // fragments per row per lane
+    static constexpr int QS = D * E + 16;                   // padded LDS row of a probe query (bytes)
+    static constexpr int HEAD_BYTES = kProbes * QS;
+    static constexpr int GC = (36 * 1024) / HEAD_BYTES > 0 ? (36 * 1024) / HEAD_BYTES : 1;   // heads staged in LDS at once
+    static constexpr int CPR = D * E / 16;                  // 16-byte chunks per row
 };
 
 template <typename T, int D>
@@ -32,236 +42,273 @@ __device__ __forceinline__ void load_row_frags(const T* row, int h, uintx4 (&f)[
         f[c] = load16(row + c * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
 }
 
-// ---------------------------------------------------------------- pass 1
-template <typename T, int D>
-__global__ __launch_bounds__(256) void score_rowstats_kernel(
+// PASS 1: partial[(bh * nsplit + split) * 64 + probe] = (raw-logit maximum, sum of exp2((s - max) * c))
+// PASS 2: mass / rank of the workgroup's keys, from bias[bh * 64 + probe] = max * c + log2(sum)
+template <typename T, int D, int PASS>
+__global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
     const T* __restrict__ Q, const T* __restrict__ K,
     int64_t qs0, int64_t qs1, int64_t qs2, int64_t ks0, int64_t ks1, int64_t ks2,
-    ProbeList probes, int m, int n, int n_eff, float c, float2* __restrict__ partial,
-    int nsplit, int keys_per_split, int Hq, int Hkv)
+    ProbeList probes, int m, int n, int n_eff, float c, float2* __restrict__ partial, int nsplit,
+    const float* __restrict__ bias, float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv)
 {
-    constexpr int CH = ScoreCfg<T, D>::CH;
-    __shared__ float2 wave_stats[4][kNB * 32];
-    const int split = blockIdx.x;
-    const int bh = blockIdx.y, b = bh / Hq, head = bh - b * Hq, g = head / (Hq / Hkv);
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
-
-    uintx4 qf[kNB][CH];
-    int Pm[kNB];
-#pragma unroll
-    for (int nb = 0; nb < kNB; ++nb) {
-        const int pc = nb * 32 + i;
-        const int P = probes.pos[min(pc, m - 1)];
-        Pm[nb] = pc < m ? P : -1;
-        load_row_frags<T, D>(Q + b * qs0 + head * qs1 + (int64_t)P * qs2, h, qf[nb]);
-    }
-    float m_run[kNB], l_run[kNB];
-#pragma unroll
-    for (int nb = 0; nb < kNB; ++nb) { m_run[nb] = -INFINITY; l_run[nb] = 0.f; }
-
-    const T* Kb = K + b * ks0 + g * ks1;
-    const int j_begin = split * keys_per_split;
-    const int j_end = min(n_eff, j_begin + keys_per_split);
-    for (int jb = j_begin + w * 32; jb < j_end; jb += 128) {
-        uintx4 kf[CH];
-        load_row_frags<T, D>(Kb + (int64_t)min(jb + i, n - 1) * ks2, h, kf);
-#pragma unroll
-        for (int nb = 0; nb < kNB; ++nb) {
-            floatx16 acc = {0};
-#pragma unroll
-            for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(kf[cc], qf[nb][cc], acc);
-            // acc[r]: key jb + acc_row(r, h), probe column nb*32 + i
-            float s[16], mx = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = jb + acc_row(r, h);
-                s[r] = key > Pm[nb] ? -INFINITY : acc[r] * c;
-                mx = fmaxf(mx, s[r]);
-            }
-            const float m_new = fmaxf(m_run[nb], mx);
-            if (m_new > -INFINITY) {
-                float sum = 0.f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sum += fast_exp2(s[r] - m_new);
-                l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - m_new) + sum;
-                m_run[nb] = m_new;
-            }
-        }
-    }
-    // merge the two lanes that share a probe column, then the four waves
-#pragma unroll
-    for (int nb = 0; nb < kNB; ++nb) {
-        const float m2 = __shfl_xor(m_run[nb], 32), l2 = __shfl_xor(l_run[nb], 32);
-        const float M = fmaxf(m_run[nb], m2);
-        float L = 0.f;
-        if (M > -INFINITY) L = l_run[nb] * fast_exp2(m_run[nb] - M) + l2 * fast_exp2(m2 - M);
-        if (h == 0) wave_stats[w][nb * 32 + i] = make_float2(M, L);
-    }
-    __syncthreads();
-    if (tid < kNB * 32) {
-        float M = -INFINITY;
-#pragma unroll
-        for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, wave_stats[ww][tid].x);
-        float L = 0.f;
-        if (M > -INFINITY) {
-#pragma unroll
-            for (int ww = 0; ww < 4; ++ww) L += wave_stats[ww][tid].y * fast_exp2(wave_stats[ww][tid].x - M);
-        }
-        partial[((int64_t)bh * nsplit + split) * (kNB * 32) + tid] = make_float2(M, L);
-    }
-}
-
-// ---------------------------------------------------------------- pass 2
-template <typename T, int D, int KB>
-__global__ __launch_bounds__(256) void score_colsum_kernel(
-    const T* __restrict__ Q, const T* __restrict__ K,
-    int64_t qs0, int64_t qs1, int64_t qs2, int64_t ks0, int64_t ks1, int64_t ks2,
-    ProbeList probes, int m, int n, int n_eff, float c, const float2* __restrict__ partial,
-    int nsplit, float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv)
-{
-    constexpr int CH = ScoreCfg<T, D>::CH;
-    __shared__ int sp[kNB * 32];
-    __shared__ float row_bias[kMaxGroup][kNB * 32];    // log2 of the row's softmax denominator
+    using C = ScoreCfg<T, D>;
+    constexpr int CH = C::CH;
+    extern __shared__ __attribute__((aligned(16))) char smem[];     // [gc][64] padded probe rows
+    __shared__ int sp[kProbes];
+    __shared__ __attribute__((aligned(16))) float row_bias[kMaxGroup][kProbes];
     const int G = Hq / Hkv;
     const int u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
-    const int block_begin = blockIdx.x * (128 * KB);
+    const int block_begin = blockIdx.x * kScoreKeys;
 
-    if (block_begin >= n_eff) {          // no probe row sees these keys
-        for (int j = block_begin + tid; j < min(n, block_begin + 128 * KB); j += 256) {
+    if (PASS == 2 && block_begin >= n_eff) {          // no probe row sees these keys
+        for (int j = block_begin + tid; j < min(n, block_begin + kScoreKeys); j += kScoreThreads) {
             mass[(int64_t)u * n + j] = 0.f;
             if (rank) rank[(int64_t)u * n + j] = 0.f;
         }
         return;
     }
-    if (tid < kNB * 32) sp[tid] = tid < m ? probes.pos[tid] : -1;
-    for (int t = tid; t < G * kNB * 32; t += 256) {
-        const int hh = t / (kNB * 32), pc = t - hh * (kNB * 32);
-        const float2* p = partial + ((int64_t)(b * Hq + g * G + hh) * nsplit) * (kNB * 32) + pc;
-        float M = -INFINITY;
-        for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[(int64_t)s * (kNB * 32)].x);
-        float L = 0.f;
-        if (M > -INFINITY)
-            for (int s = 0; s < nsplit; ++s) {
-                const float2 v = p[(int64_t)s * (kNB * 32)];
-                L += v.y * fast_exp2(v.x - M);
-            }
-        row_bias[hh][pc] = (pc < m && L > 0.f) ? M + __log2f(L) : INFINITY;
-    }
+    if (tid < kProbes) sp[tid] = probes.pos[tid];          // -1 beyond m
+    if (PASS == 2)
+        for (int t = tid; t < G * kProbes; t += kScoreThreads)
+            (&row_bias[0][0])[t] = bias[(int64_t)(b * Hq + g * G) * kProbes + t];
     __syncthreads();
     const int Pmin = sp[0];
+    const bool has_pad = m < kProbes;
 
-    float colsum[KB];
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb) colsum[kb] = 0.f;
+    // this wave's 32 keys stay in registers for every head of the group
+    const int jb = block_begin + w * 32;
+    const bool live = jb < n_eff;                           // wave-uniform
+    uintx4 kf[CH];
+    load_row_frags<T, D>(K + b * ks0 + g * ks1 + (int64_t)min(jb + i, n - 1) * ks2, h, kf);
+    const bool masked = has_pad || jb + 31 > Pmin;          // wave-uniform
 
-    const T* Kb = K + b * ks0 + g * ks1;
-    for (int hh = 0; hh < G; ++hh) {
-        const int head = g * G + hh;
-        uintx4 qf[kNB][CH];
-        float rb[kNB][16];
+    float colsum = 0.f;                                     // PASS 2
+    float2* wstat = reinterpret_cast<float2*>(smem + C::GC * C::HEAD_BYTES);   // PASS 1: [wave][head of chunk][nb][lane]
+
+    // Probe rows travel global -> registers -> LDS one chunk of GC heads at a time; the next chunk
+    // is requested before the current one is consumed, so its latency hides under the matrix work.
+    constexpr int NPRE = C::GC * kProbes * C::CPR / kScoreThreads;
+    static_assert(NPRE * kScoreThreads == C::GC * kProbes * C::CPR, "chunk must divide evenly over the threads");
+    uintx4 pre[NPRE];
+    auto fetch_chunk = [&](int h0) {
+        const int total = min(C::GC, G - h0) * kProbes * C::CPR;
 #pragma unroll
-        for (int nb = 0; nb < kNB; ++nb) {
-            const int P = sp[min(nb * 32 + i, m - 1)];
-            load_row_frags<T, D>(Q + b * qs0 + head * qs1 + (int64_t)P * qs2, h, qf[nb]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) rb[nb][r] = row_bias[hh][nb * 32 + acc_row(r, h)];
+        for (int q = 0; q < NPRE; ++q) {
+            const int t = min(tid + q * kScoreThreads, total - 1);
+            const int row = t / C::CPR, cc = t - row * C::CPR;
+            const int hh = row / kProbes, pc = row - hh * kProbes;
+            const T* src = Q + b * qs0 + (g * G + h0 + hh) * qs1 + (int64_t)sp[min(pc, m - 1)] * qs2;
+            pre[q] = load16(src + cc * Elem<T>::kPerFrag);
         }
+    };
+    fetch_chunk(0);
+    for (int h0 = 0; h0 < G; h0 += C::GC) {
+        const int gc = min(C::GC, G - h0);
+        if (h0) __syncthreads();                            // previous chunk fully consumed
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const int jb = block_begin + (w * KB + kb) * 32;
-            if (jb >= n_eff) continue;
-            const int j = jb + i;                       // this lane's key column
-            uintx4 kf[CH];
-            load_row_frags<T, D>(Kb + (int64_t)min(j, n - 1) * ks2, h, kf);
-            const bool masked = jb + 31 > Pmin;
-            float sum = 0.f;
+        for (int q = 0; q < NPRE; ++q) {
+            const int t = tid + q * kScoreThreads;
+            const int row = t / C::CPR, cc = t - row * C::CPR;
+            store16(smem + row * C::QS + cc * 16, pre[q]);  // rows beyond gc heads hold duplicates, never read
+        }
+        __syncthreads();
+        if (h0 + C::GC < G) fetch_chunk(h0 + C::GC);
+#pragma unroll 1
+        for (int hh = 0; hh < gc; ++hh) {
+            const char* qh = smem + hh * C::HEAD_BYTES;
 #pragma unroll
             for (int nb = 0; nb < kNB; ++nb) {
-                floatx16 acc = {0};
+                float2 stat = make_float2(-INFINITY, 0.f);
+                if (live) {
+                    uintx4 qf[CH];
 #pragma unroll
-                for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(qf[nb][cc], kf[cc], acc);
-                // acc[r]: probe row nb*32 + acc_row(r, h), key column j
-                if (masked) {
+                    for (int cc = 0; cc < CH; ++cc)
+                        qf[cc] = *reinterpret_cast<const uintx4*>(qh + (nb * 32 + i) * C::QS + cc * 32 + h * 16);
+                    floatx16 acc = {0};
+                    if (PASS == 1) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float p = fast_exp2(acc[r] * c - rb[nb][r]);
-                        sum += j > sp[nb * 32 + acc_row(r, h)] ? 0.f : p;
+                        for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(kf[cc], qf[cc], acc);
+                        // acc[r]: key jb + acc_row(r, h), probe column nb*32 + i  (raw logit)
+                        float sv[16], mx = -INFINITY;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) sv[r] = acc[r];
+                        if (masked) {
+                            const int Pm = sp[nb * 32 + i];
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                if (jb + acc_row(r, h) > Pm) sv[r] = -INFINITY;
+                        }
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sv[r]);
+                        float sum = 0.f;
+                        if (mx > -INFINITY) {               // statistics of this lane's 16 keys only
+                            const float mc = mx * c;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(sv[r], c, -mc));
+                        }
+                        stat = make_float2(mx, sum);
+                    } else {
+#pragma unroll
+                        for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(qf[cc], kf[cc], acc);
+                        // acc[r]: probe row nb*32 + acc_row(r, h), key column jb + i
+                        float rb[16];
+#pragma unroll
+                        for (int a = 0; a < 4; ++a) {
+                            const floatx4 v = *reinterpret_cast<const floatx4*>(&row_bias[h0 + hh][nb * 32 + 8 * a + 4 * h]);
+                            rb[4 * a] = v[0]; rb[4 * a + 1] = v[1]; rb[4 * a + 2] = v[2]; rb[4 * a + 3] = v[3];
+                        }
+                        float sum = 0.f;
+                        if (masked) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const float p = fast_exp2(fmaf(acc[r], c, -rb[r]));
+                                sum += jb + i > sp[nb * 32 + acc_row(r, h)] ? 0.f : p;
+                            }
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c, -rb[r]));
+                        }
+                        colsum += sum;
                     }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sum += fast_exp2(acc[r] * c - rb[nb][r]);
                 }
+                if (PASS == 1) wstat[((w * C::GC + hh) * kNB + nb) * 64 + lane] = stat;
             }
-            colsum[kb] += sum;
+        }
+        if (PASS == 1) {
+            // merge the 4 waves x 2 half-waves that saw each (head, probe row) and emit the slice partial
+            __syncthreads();
+            for (int t = tid; t < gc * kProbes; t += kScoreThreads) {
+                const int hh = t / kProbes, pc = t - hh * kProbes, nb = pc >> 5, ii = pc & 31;
+                float M = -INFINITY;
+#pragma unroll
+                for (int ww = 0; ww < kScoreWaves; ++ww)
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf)
+                        M = fmaxf(M, wstat[((ww * C::GC + hh) * kNB + nb) * 64 + hf * 32 + ii].x);
+                float L = 0.f;
+                if (M > -INFINITY) {
+#pragma unroll
+                    for (int ww = 0; ww < kScoreWaves; ++ww)
+#pragma unroll
+                        for (int hf = 0; hf < 2; ++hf) {
+                            const float2 v = wstat[((ww * C::GC + hh) * kNB + nb) * 64 + hf * 32 + ii];
+                            L += v.y * fast_exp2((v.x - M) * c);
+                        }
+                }
+                partial[((int64_t)(b * Hq + g * G + h0 + hh) * nsplit + blockIdx.x) * kProbes + pc] = make_float2(M, L);
+            }
         }
     }
-    const float inv_g = 1.f / (float)G;
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-        const int jb = block_begin + (w * KB + kb) * 32;
-        const float a = (colsum[kb] + __shfl_xor(colsum[kb], 32)) * inv_g;
+
+    if (PASS == 2) {
+        const float a = (colsum + __shfl_xor(colsum, 32)) / (float)G;
         const int j = jb + i;
         if (h == 0 && j < n) {
             int cnt = 0;
-            for (int t = 0; t < m; ++t) cnt += sp[t] >= j ? 1 : 0;
+            if (j <= Pmin) cnt = m;
+            else for (int t = 0; t < m; ++t) cnt += sp[t] >= j ? 1 : 0;
             mass[(int64_t)u * n + j] = a / (float)m;
             if (rank) rank[(int64_t)u * n + j] = cnt > 0 ? a / (float)cnt : 0.f;
         }
     }
 }
 
-// ---------------------------------------------------------------- host side
-struct ScorePlan { int n_eff, nsplit, keys_per_split, KB; };
+// Merge the per-slice statistics of every (head, probe row) into one exponent offset
+// bias = max * c + log2(sum), so that exp2(s * c - bias) is the normalised probability.
+// Block = 64 probe rows x 8 slice groups.
+__global__ __launch_bounds__(512) void score_rowfinal_kernel(
+    const float2* __restrict__ partial, int nsplit, int m, float c, float* __restrict__ bias)
+{
+    __shared__ float2 red[8][kProbes];
+    const int bh = blockIdx.x, pc = threadIdx.x & 63, sg = threadIdx.x >> 6;
+    const float2* p = partial + (int64_t)bh * nsplit * kProbes + pc;
+    float M = -INFINITY, L = 0.f;
+    for (int s0 = sg; s0 < nsplit; s0 += 32) {              // 4 independent loads per round
+        float2 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int s = s0 + 8 * q;
+            v[q] = s < nsplit ? p[(int64_t)s * kProbes] : make_float2(-INFINITY, 0.f);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float Mn = fmaxf(M, v[q].x);
+            if (Mn > -INFINITY) L = L * fast_exp2((M - Mn) * c) + v[q].y * fast_exp2((v[q].x - Mn) * c);
+            M = Mn;
+        }
+    }
+    red[sg][pc] = make_float2(M, L);
+    __syncthreads();
+    if (sg == 0) {
+        float Mt = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) Mt = fmaxf(Mt, red[q][pc].x);
+        float Lt = 0.f;
+        if (Mt > -INFINITY) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) Lt += red[q][pc].y * fast_exp2((red[q][pc].x - Mt) * c);
+        }
+        bias[(int64_t)bh * kProbes + pc] = (pc < m && Lt > 0.f) ? Mt * c + __log2f(Lt) : INFINITY;
+    }
+}
 
-static ScorePlan plan_score(const zipvl_dims& d, const int32_t* probe_pos, int m) {
-    ScorePlan p;
-    p.n_eff = probe_pos ? probe_pos[m - 1] + 1 : d.n;
-    const int heads = d.B * d.Hq;
-    int want = (1024 + heads - 1) / heads;
-    want = want < 1 ? 1 : (want > kMaxSplit ? kMaxSplit : want);
-    int per = (p.n_eff + want - 1) / want;
-    per = ((per + 127) / 128) * 128;
-    p.keys_per_split = per;
-    p.nsplit = (p.n_eff + per - 1) / per;
-    const int units = d.B * d.Hkv;
-    p.KB = 1;
-    for (int kb = 4; kb >= 1; kb >>= 1)
-        if ((int64_t)((d.n + 128 * kb - 1) / (128 * kb)) * units >= 512) { p.KB = kb; break; }
-    return p;
+// ---------------------------------------------------------------- host side
+static int score_splits(const zipvl_dims& d) { return (d.n + kScoreKeys - 1) / kScoreKeys; }
+
+static size_t score_partial_bytes(const zipvl_dims& d) {
+    return (size_t)d.B * d.Hq * score_splits(d) * kProbes * sizeof(float2);
 }
 
 size_t score_workspace_bytes(const zipvl_dims& d, int m) {
     (void)m;
-    return (size_t)d.B * d.Hq * kMaxSplit * (kNB * 32) * sizeof(float2);
+    return score_partial_bytes(d) + (size_t)d.B * d.Hq * kProbes * sizeof(float);
 }
 
 template <typename T, int D>
 static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
-                          const ScorePlan& p, float scale, float* mass, float* rank, void* ws, hipStream_t st)
+                          int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
 {
+    using C = ScoreCfg<T, D>;
     const float c = scale * kLog2e;
     float2* partial = (float2*)ws;
+    float* bias = (float*)((char*)ws + score_partial_bytes(d));
+    const int G = d.Hq / d.Hkv, units = d.B * d.Hkv;
+    // probe rows of GC heads, then the per-wave statistics of pass 1
+    const size_t lds = (size_t)C::GC * C::HEAD_BYTES + (size_t)kScoreWaves * C::GC * kNB * 64 * sizeof(float2);
+    (void)G;
+    static bool attr_done = false;
+    if (!attr_done) {
+        const int cap = 64 * 1024;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
+            return set_error(ZIPVL_EHIP, "score: cannot reserve LDS for the probe rows");
+        attr_done = true;
+    }
+    const int nsplit = (n_eff + kScoreKeys - 1) / kScoreKeys;
     {
         KernelTimer tm(ZIPVL_K_SCORE_ROWSTATS, st);
-        hipLaunchKernelGGL((score_rowstats_kernel<T, D>), dim3(p.nsplit, d.B * d.Hq), dim3(256), 0, st,
+        hipLaunchKernelGGL((score_pass_kernel<T, D, 1>), dim3(nsplit, units), dim3(kScoreThreads), lds, st,
             (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-            d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, p.n_eff, c, partial,
-            p.nsplit, p.keys_per_split, d.Hq, d.Hkv);
+            d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, partial, nsplit,
+            (const float*)nullptr, (float*)nullptr, (float*)nullptr, d.Hq, d.Hkv);
     }
     int rc = check_launch("score_rowstats");
     if (rc) return rc;
-#define ZIPVL_COLSUM(KBV)                                                                          \
-    hipLaunchKernelGGL((score_colsum_kernel<T, D, KBV>),                                           \
-        dim3((d.n + 128 * KBV - 1) / (128 * KBV), d.B * d.Hkv), dim3(256), 0, st,                  \
-        (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],                  \
-        d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, p.n_eff, c,                    \
-        (const float2*)partial, p.nsplit, mass, rank, d.Hq, d.Hkv)
+    {
+        KernelTimer tm(ZIPVL_K_SCORE_ROWFINAL, st);
+        hipLaunchKernelGGL(score_rowfinal_kernel, dim3(d.B * d.Hq), dim3(512), 0, st,
+            (const float2*)partial, nsplit, m, c, bias);
+    }
+    rc = check_launch("score_rowfinal");
+    if (rc) return rc;
     KernelTimer tm(ZIPVL_K_SCORE_COLSUM, st);
-    if (p.KB == 4) ZIPVL_COLSUM(4);
-    else if (p.KB == 2) ZIPVL_COLSUM(2);
-    else ZIPVL_COLSUM(1);
-#undef ZIPVL_COLSUM
+    hipLaunchKernelGGL((score_pass_kernel<T, D, 2>), dim3(score_splits(d), units), dim3(kScoreThreads), lds, st,
+        (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
+        d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, (float2*)nullptr, nsplit,
+        (const float*)bias, mass, rank, d.Hq, d.Hkv);
     return check_launch("score_colsum");
 }
 
@@ -271,13 +318,13 @@ int launch_score(const void* Q, const void* K, const zipvl_dims& d, const int32_
     if (d.Hq / d.Hkv > kMaxGroup) return set_error(ZIPVL_ESHAPE, "score: Hq/Hkv = %d exceeds %d", d.Hq / d.Hkv, kMaxGroup);
     ProbeList pl;
     for (int t = 0; t < ZIPVL_MAX_PROBES; ++t) pl.pos[t] = t < m ? probe_pos[t] : -1;
-    const ScorePlan p = plan_score(d, probe_pos, m);
+    const int n_eff = probe_pos[m - 1] + 1;
     if (d.dtype == ZIPVL_BF16) {
-        if (d.d == 128) return launch_score_t<__bf16, 128>(Q, K, d, pl, m, p, scale, mass, rank, ws, st);
-        return launch_score_t<__bf16, 64>(Q, K, d, pl, m, p, scale, mass, rank, ws, st);
+        if (d.d == 128) return launch_score_t<__bf16, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+        return launch_score_t<__bf16, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
     }
-    if (d.d == 128) return launch_score_t<float, 128>(Q, K, d, pl, m, p, scale, mass, rank, ws, st);
-    return launch_score_t<float, 64>(Q, K, d, pl, m, p, scale, mass, rank, ws, st);
+    if (d.d == 128) return launch_score_t<float, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    return launch_score_t<float, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
 }
 
 }  // namespace zipvl

@@ -14,8 +14,9 @@
 //     v* is the k-th largest value, found by the same descent on counts;
 //   * the set is written in ascending position by a ballot-ranked stream
 //     compaction (each wave owns a contiguous span of positions).
-// One 1024-thread workgroup per selection unit; the score vectors stay in L2
-// (72 KB per vector at n = 18432) and are re-read once per digit.
+// One 1024-thread workgroup per selection unit.  Up to n = 26624 the order-preserving keys of
+// the vector in use are held in LDS (read from memory once, coalesced); longer vectors are
+// re-read per digit.
 #include "launch.h"
 
 namespace zipvl {
@@ -38,11 +39,11 @@ struct SelShared {
     int k;
 };
 
-// Order-preserving map fp32 -> uint32 (larger float <=> larger key); -0 and +0 coincide.
+// Order-preserving 31-bit key of a non-negative fp32 score: its bit pattern.  Scores are >= 0 by
+// contract; anything with the sign bit set (-0 included) is ordered and summed as zero.
 __device__ __forceinline__ uint32_t orderable(float x) {
-    uint32_t b = __float_as_uint(x);
-    if ((b << 1) == 0) b = 0;
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    const uint32_t b = __float_as_uint(x);
+    return (b & 0x80000000u) ? 0u : b;
 }
 
 // floor(x * 2^40) for finite x in [0, 2^24), exact, integer-only.
@@ -56,11 +57,42 @@ __device__ __forceinline__ unsigned long long fixed40(float x) {
     return (-sh >= 24) ? 0ull : (M >> (-sh));
 }
 
-// One descent over the four 8-bit digits.  WITH_SUM: cross on the integer sum
+// Where the keys of a unit live while the kernel runs: in LDS (filled once per vector with
+// coalesced reads, then read conflict-free by every pass) when they fit, otherwise every pass
+// re-reads the fp32 vector from global memory (any n).
+struct Keys {
+    const uint32_t* lds;      // n order-preserving keys, or nullptr
+    const float* x;
+    int n;
+    template <typename F>
+    __device__ __forceinline__ void for_each(F&& f) const {
+        if (lds) {
+#pragma unroll 4
+            for (int j = threadIdx.x; j < n; j += kSelThreads) f(j, lds[j]);
+        } else {
+#pragma unroll 4
+            for (int j = threadIdx.x; j < n; j += kSelThreads) f(j, orderable(x[j]));
+        }
+    }
+    __device__ __forceinline__ uint32_t at(int j) const { return lds ? lds[j] : orderable(x[j]); }
+};
+
+__device__ __forceinline__ void fill_keys(uint32_t* dst, const float* __restrict__ x, int n) {
+#pragma unroll 8
+    for (int j = threadIdx.x; j < n; j += kSelThreads) dst[j] = orderable(x[j]);
+}
+
+__device__ __forceinline__ unsigned long long fixed40_of_key(uint32_t key) {
+    return fixed40(__uint_as_float(key));
+}
+
+// One descent over the 31 key bits in four digits, exponent byte first (8 + 8 + 8 + 7 bits).  The
+// first digit sees every element and uses kRep histogram replicas; later digits only see the
+// elements that share the prefix and use one.  WITH_SUM: cross on the integer sum
 // (target = sh.target, fixed after the first digit from the grand total);
 // otherwise cross on the element count (target = cnt_target).
 template <bool WITH_SUM>
-__device__ void radix_descent(const float* __restrict__ x, int n, double tau, uint32_t cnt_target,
+__device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
                               SelShared& sh, uint32_t& prefix_out, uint32_t& base_cnt_out,
                               unsigned long long& base_sum_out, bool& degenerate)
 {
@@ -69,29 +101,28 @@ __device__ void radix_descent(const float* __restrict__ x, int n, double tau, ui
     unsigned long long base_sum = 0;
     degenerate = false;
     for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        for (int i = tid; i < 256 * kRep; i += kSelThreads) {
+        const int shift = pass < 3 ? 23 - 8 * pass : 0;
+        const uint32_t dmask = pass < 3 ? 255u : 127u;
+        const int rep = pass == 0 ? kRep : 1;
+        for (int i = tid; i < 256 * rep; i += kSelThreads) {
             sh.cnt[i] = 0;
             if (WITH_SUM) sh.sum[i] = 0;
         }
         __syncthreads();
-        for (int j = tid; j < n; j += kSelThreads) {
-            const float v = x[j];
-            const uint32_t key = orderable(v);
+        keys.for_each([&](int, uint32_t key) {
             if ((key & mask) == prefix) {
-                const int slot = ((key >> shift) & 255) * kRep + (tid & (kRep - 1));
+                const int slot = ((key >> shift) & dmask) * rep + (tid & (rep - 1));
                 atomicAdd(&sh.cnt[slot], 1u);
-                if (WITH_SUM) atomicAdd(&sh.sum[slot], fixed40(v));
+                if (WITH_SUM) atomicAdd(&sh.sum[slot], fixed40_of_key(key));
             }
-        }
+        });
         __syncthreads();
         if (tid < 256) {
             uint32_t c = 0;
             unsigned long long s = 0;
-#pragma unroll
-            for (int r = 0; r < kRep; ++r) {
-                c += sh.cnt[tid * kRep + r];
-                if (WITH_SUM) s += sh.sum[tid * kRep + r];
+            for (int r = 0; r < rep; ++r) {
+                c += sh.cnt[tid * rep + r];
+                if (WITH_SUM) s += sh.sum[tid * rep + r];
             }
             sh.bin_cnt[tid] = c;
             sh.bin_sum[tid] = s;
@@ -148,7 +179,7 @@ __device__ void radix_descent(const float* __restrict__ x, int n, double tau, ui
         __syncthreads();
         if (WITH_SUM && sh.target == 0ull) { degenerate = true; break; }   // all scores zero
         prefix |= sh.sel_digit << shift;
-        mask |= 255u << shift;
+        mask |= dmask << shift;
         base_cnt = sh.base_cnt;
         base_sum = sh.base_sum;
     }
@@ -159,28 +190,35 @@ __device__ void radix_descent(const float* __restrict__ x, int n, double tau, ui
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ mass_all, const float* __restrict__ rank_all, int n, double tau,
-    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out)
+    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out, int keys_in_lds)
 {
     __shared__ SelShared sh;
+    extern __shared__ uint32_t lds_keys[];             // n entries when keys_in_lds
     const int u = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* mass = mass_all + (int64_t)u * n;
     const float* rank = rank_all ? rank_all + (int64_t)u * n : mass;
     int32_t* idx = idx_all + (int64_t)u * n;
 
-    // ---- how many (Eq. (7)) ----
-    int k;
     if (tau >= 1.0) {
-        k = n;
-    } else {
+        if (tid == 0) k_out[u] = n;
+        for (int j = tid; j < n; j += kSelThreads) idx[j] = j;
+        return;
+    }
+
+    // ---- how many (Eq. (7)) ----
+    Keys mk{keys_in_lds ? lds_keys : nullptr, mass, n};
+    if (keys_in_lds) { fill_keys(lds_keys, mass, n); __syncthreads(); }
+    int k;
+    {
         uint32_t prefix, base_cnt;
         unsigned long long base_sum;
         bool degenerate;
-        radix_descent<true>(mass, n, tau, 0u, sh, prefix, base_cnt, base_sum, degenerate);
+        radix_descent<true>(mk, tau, 0u, sh, prefix, base_cnt, base_sum, degenerate);
         if (tid == 0) {
             int kk = 1;
             if (!degenerate) {
-                const unsigned long long qv = fixed40(__uint_as_float(prefix ^ 0x80000000u));
+                const unsigned long long qv = fixed40_of_key(prefix);
                 const unsigned long long need = sh.target - base_sum;           // >= 1
                 kk = (int)(base_cnt + (qv ? (need + qv - 1) / qv : 1ull));
             }
@@ -197,20 +235,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __syncthreads();
 
     // ---- which (Eq. (9)): k-th largest normalised score v*, ties to the lower index ----
+    Keys rk{keys_in_lds ? lds_keys : nullptr, rank, n};
+    if (keys_in_lds && rank != mass) { fill_keys(lds_keys, rank, n); __syncthreads(); }
     uint32_t vstar, cnt_gt;
     {
         unsigned long long unused;
         bool dg;
-        radix_descent<false>(rank, n, tau, (uint32_t)k, sh, vstar, cnt_gt, unused, dg);
+        radix_descent<false>(rk, tau, (uint32_t)k, sh, vstar, cnt_gt, unused, dg);
     }
     const uint32_t need_eq = (uint32_t)k - cnt_gt;     // ties at v* that are kept (>= 1)
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
     // ---- ascending emission: wave w owns positions [w*seg, (w+1)*seg) ----
     const int seg = (((n + kSelWaves - 1) / kSelWaves) + 63) & ~63;
     const int j0 = wave * seg, j1 = min(n, j0 + seg);
     uint32_t wgt = 0, weq = 0;
+#pragma unroll 4
     for (int j = j0 + lane; j - lane < j1; j += 64) {
-        const uint32_t key = (j < j1) ? orderable(rank[j]) : 0u;
+        const uint32_t key = (j < j1) ? rk.at(j) : 0u;
         wgt += __popcll(__ballot(j < j1 && key > vstar));
         weq += __popcll(__ballot(j < j1 && key == vstar));
     }
@@ -218,9 +260,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __syncthreads();
     uint32_t gt_before = 0, eq_before = 0;
     for (int w = 0; w < wave; ++w) { gt_before += sh.wave_gt[w]; eq_before += sh.wave_eq[w]; }
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+#pragma unroll 4
     for (int j = j0 + lane; j - lane < j1; j += 64) {
-        const uint32_t key = (j < j1) ? orderable(rank[j]) : 0u;
+        const uint32_t key = (j < j1) ? rk.at(j) : 0u;
         const bool gt = j < j1 && key > vstar;
         const bool eq = j < j1 && key == vstar;
         const unsigned long long bg = __ballot(gt), be = __ballot(eq);
@@ -236,11 +278,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
 }
 
+constexpr int kSelMaxLdsKeys = 26624;      // 104 KiB of keys beside the 52 KiB of histograms
+
 int launch_select(const float* mass, const float* rank, int units, int n, double tau,
                   int32_t* idx, int32_t* k, hipStream_t st)
 {
+    const int in_lds = n <= kSelMaxLdsKeys ? 1 : 0;
+    const size_t dyn = in_lds ? (size_t)n * sizeof(uint32_t) : 0;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kSelMaxLdsKeys * (int)sizeof(uint32_t)) != hipSuccess)
+            return set_error(ZIPVL_EHIP, "select: cannot reserve LDS for the keys");
+        attr_done = true;
+    }
     KernelTimer tm(ZIPVL_K_SELECT, st);
-    hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), 0, st, mass, rank, n, tau, idx, k);
+    hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), dyn, st, mass, rank, n, tau, idx, k, in_lds);
     return check_launch("select");
 }
 

@@ -197,6 +197,12 @@ def test_attention_bf16_gqa_ragged():
     _attention_case(2, 6, 2, 700, 128, "bf16", [700, 257, 64, 385], seed=2)
 
 
+def test_attention_kept_count_on_tile_boundaries():
+    say("attention bf16 d=128, k = 128, 256, 384 and n (dropped tail must be cleared)")
+    _attention_case(2, 4, 2, 640, 128, "bf16", [128, 256, 384, 640], seed=9)
+    _attention_case(1, 2, 2, 384, 64, "f32", [384, 128], seed=10)
+
+
 def test_attention_bf16_d64_and_fp32_d128():
     say("attention bf16 d=64")
     _attention_case(1, 2, 2, 300, 64, "bf16", [300, 129], seed=3)
