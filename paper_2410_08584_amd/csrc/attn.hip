@@ -7,8 +7,9 @@
 //          transposed V is what lets the P.V product read both MFMA operands
 //          as contiguous fragments (the contraction runs over keys).
 //   flash  one workgroup = 128 kept queries of one query head (4 waves x 32
-//          rows).  K / V^T tiles of 64 keys are staged through LDS (double
-//          buffered, one barrier per tile) and shared by the four waves.
+//          rows).  K / V^T tiles of 64 keys are loaded straight into LDS
+//          (double buffered, one barrier per tile) and shared by the four waves;
+//          the S^T product of the next tile overlaps the softmax of the current.
 //          S^T = K Q^T and O^T = V^T P^T are taken on 32x32 MFMA tiles, so a
 //          lane owns one query column: the online-softmax statistics are
 //          per-lane scalars and only the running maximum crosses lanes (one
@@ -32,14 +33,13 @@ struct AttnCfg {
     static constexpr int E = Elem<T>::kBytes;
     static constexpr int CH = D / Elem<T>::kPerChunk;       // Q/K fragments per row per lane
     static constexpr int ODB = D / 32;                       // 32-row blocks of O^T
-    static constexpr int KS = D * E + 16;                    // LDS row stride of the K tile (bytes)
-    static constexpr int VS = kBN * E + 16;                  // LDS row stride of the V^T tile (bytes)
-    static constexpr int KCPR = D * E / 16;                  // 16-byte chunks per K row
-    static constexpr int VCPR = kBN * E / 16;                // 16-byte chunks per V^T row
-    static constexpr int CPT = kBN * D * E / 16 / 256;       // chunks per thread per tile (K or V^T)
-    static constexpr int K_TILE = kBN * KS;
-    static constexpr int V_TILE = D * VS;
-    static constexpr int LDS_BYTES = 2 * (K_TILE + V_TILE);
+    // LDS tiles are unpadded; the 16-byte chunks of a row are XOR-swizzled with (row & 7) instead, so
+    // that any 8 consecutive rows read at the same logical chunk hit 8 different bank groups.
+    static constexpr int KRB = D * E;                        // bytes per K row
+    static constexpr int VRB = kBN * E;                      // bytes per V^T row
+    static constexpr int TILE_BYTES = kBN * D * E;           // one K tile = one V^T tile
+    static constexpr int NLD = TILE_BYTES / 1024 / 4;        // 1-KiB direct-to-LDS loads per wave per tile
+    static constexpr int LDS_BYTES = 4 * TILE_BYTES;         // two K and two V^T buffers
     static constexpr int NVF = (E == 2 ? 2 : 4) * ODB;       // V^T operand fragments per 32 keys per lane
     static constexpr int MIN_WAVES = (E == 2) ? 2 : 1;       // bf16: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs)
 };
@@ -96,82 +96,91 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
 }
 
 // ------------------------------------------------------------------ flash
+// byte offset of logical 16-byte chunk `c` in a swizzled LDS row (sw = row & 7)
+__device__ __forceinline__ int swz_chunk(int c, int sw) { return (c ^ sw) << 4; }
+
+// One tile (TILE_BYTES contiguous in global memory) -> one LDS buffer, without passing through
+// registers: every wave issues NLD loads of 1 KiB, lane L of a load writes LDS bytes [16 L, 16 L + 16)
+// of that KiB, and picks the global chunk that belongs there under the row swizzle.
 template <typename T, int D>
-__device__ __forceinline__ void load_tile(const char* kt, const char* vt, int tid,
-                                          uintx4 (&kr)[AttnCfg<T, D>::CPT], uintx4 (&vr)[AttnCfg<T, D>::CPT]) {
+__device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w, const int (&off)[AttnCfg<T, D>::NLD]) {
 #pragma unroll
-    for (int q = 0; q < AttnCfg<T, D>::CPT; ++q) {
-        kr[q] = load16(kt + (q * 256 + tid) * 16);
-        vr[q] = load16(vt + (q * 256 + tid) * 16);
+    for (int q = 0; q < AttnCfg<T, D>::NLD; ++q)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(gtile + off[q]),
+            (__attribute__((address_space(3))) void*)(lbuf + (q * 4 + w) * 1024), 16, 0, 0);
+}
+
+// per-lane source offsets for tile_to_lds (rows of RB bytes)
+template <int RB, int NLD>
+__device__ __forceinline__ void lds_fill_offsets(int w, int lane, int (&off)[NLD]) {
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const int o = (q * 4 + w) * 1024 + lane * 16;
+        const int r = o / RB, p = (o % RB) >> 4;
+        off[q] = r * RB + ((p ^ (r & 7)) << 4);
     }
 }
 
+// S^T = K Q^T for one 64-key tile held in LDS buffer kb: acc[blk][r] = key 32*blk + acc_row(r, h), this lane's query
 template <typename T, int D>
-__device__ __forceinline__ void stage_tile(char* ks, char* vs, int tid,
-                                           const uintx4 (&kr)[AttnCfg<T, D>::CPT], const uintx4 (&vr)[AttnCfg<T, D>::CPT]) {
+__device__ __forceinline__ void qk_tile(const char* kb, int i, int h, int sw, const uintx4 (&qf)[AttnCfg<T, D>::CH],
+                                        floatx16 (&acc)[2]) {
     using C = AttnCfg<T, D>;
 #pragma unroll
-    for (int q = 0; q < C::CPT; ++q) {
-        const int id = q * 256 + tid;
-        store16(ks + (id / C::KCPR) * C::KS + (id % C::KCPR) * 16, kr[q]);
-        store16(vs + (id / C::VCPR) * C::VS + (id % C::VCPR) * 16, vr[q]);
+    for (int blk = 0; blk < 2; ++blk) {
+        floatx16 a = {0};
+#pragma unroll
+        for (int cc = 0; cc < C::CH; ++cc) {
+            const uintx4 kf = *reinterpret_cast<const uintx4*>(kb + (blk * 32 + i) * C::KRB + swz_chunk(2 * cc + h, sw));
+            a = mma_frag<T>(kf, qf[cc], a);
+        }
+        acc[blk] = a;
     }
 }
 
-// P^T (64 keys x 32 queries, registers p[2][16]) times the V^T tile -> O^T accumulators, in two
-// halves of 32 keys (HALF = S^T block).  `load` fetches the V^T operand fragments of one half from
-// LDS, `run` consumes them.
+// O^T += V^T P^T for the 32 keys of half HALF: p[16] holds the probabilities of S^T block HALF.
 template <typename T, int D> struct PV;
 
 template <int D> struct PV<__bf16, D> {
     using C = AttnCfg<__bf16, D>;
-    // fragment (s2, db): 16-key step s = 2*HALF + s2, 32-row block db of O^T
     template <int HALF>
-    __device__ static __forceinline__ void load(const char* vs, int i, int h, uintx4 (&vf)[C::NVF]) {
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-            for (int db = 0; db < C::ODB; ++db)     // V^T rows are stored in contraction-slot order
-                vf[s2 * C::ODB + db] = *reinterpret_cast<const uintx4*>(
-                    vs + (db * 32 + i) * C::VS + (2 * HALF + s2) * 32 + h * 16);
-    }
-    __device__ static __forceinline__ void run(const uintx4 (&vf)[C::NVF], const float (&p)[16], floatx16 (&o)[C::ODB]) {
+    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const floatx16& p, floatx16 (&o)[C::ODB]) {
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-            // contraction slot t of this lane <-> key 16*s2 + 8*(t/4) + 4*h + t%4 of the half = register 8*s2 + t
+            // contraction slot t of this lane <-> key 16*s2 + 8*(t/4) + 4*h + t%4 of the half = register 8*s2 + t;
+            // V^T rows are stored in slot order, so the matching operand is one 16-byte chunk
             uintx4 bfrag;
             bfrag[0] = pack_bf16x2(p[8 * s2 + 0], p[8 * s2 + 1]);
             bfrag[1] = pack_bf16x2(p[8 * s2 + 2], p[8 * s2 + 3]);
             bfrag[2] = pack_bf16x2(p[8 * s2 + 4], p[8 * s2 + 5]);
             bfrag[3] = pack_bf16x2(p[8 * s2 + 6], p[8 * s2 + 7]);
+            const int chunk = swz_chunk(2 * (2 * HALF + s2) + h, sw);
 #pragma unroll
-            for (int db = 0; db < C::ODB; ++db) o[db] = mma_frag<__bf16>(vf[s2 * C::ODB + db], bfrag, o[db]);
+            for (int db = 0; db < C::ODB; ++db) {
+                const uintx4 vf = *reinterpret_cast<const uintx4*>(vb + (db * 32 + i) * C::VRB + chunk);
+                o[db] = mma_frag<__bf16>(vf, bfrag, o[db]);
+            }
         }
     }
 };
 
 template <int D> struct PV<float, D> {
     using C = AttnCfg<float, D>;
-    // fragment (a, db): keys 32*HALF + 8*a + 4*h + t (t = 0..3) of O^T block db
     template <int HALF>
-    __device__ static __forceinline__ void load(const char* vs, int i, int h, uintx4 (&vf)[C::NVF]) {
+    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const floatx16& p, floatx16 (&o)[C::ODB]) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int db = 0; db < C::ODB; ++db)
-                vf[a * C::ODB + db] = *reinterpret_cast<const uintx4*>(
-                    vs + (db * 32 + i) * C::VS + (32 * HALF + 8 * a + 4 * h) * 4);
-    }
-    __device__ static __forceinline__ void run(const uintx4 (&vf)[C::NVF], const float (&p)[16], floatx16 (&o)[C::ODB]) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 4; ++a) {
+            // step (a, t): this lane contributes key 32*HALF + 8*a + 4*h + t
+            const int chunk = swz_chunk(8 * HALF + 2 * a + h, sw);
 #pragma unroll
             for (int db = 0; db < C::ODB; ++db) {
-                const floatx4 v = __builtin_bit_cast(floatx4, vf[a * C::ODB + db]);
+                const floatx4 v = *reinterpret_cast<const floatx4*>(vb + (db * 32 + i) * C::VRB + chunk);
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(v[t], p[4 * a + t], o[db], 0, 0, 0);
             }
+        }
     }
 };
 
@@ -254,85 +263,85 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
 
     const int ntiles = (min(i0 + kBM, kk) + kBN - 1) / kBN;
     const int wave_first_row = i0 + 32 * w, wave_last_row = wave_first_row + 31;
+    const int my_tiles = min(ntiles, wave_last_row / kBN + 1);   // later tiles lie wholly in this wave's future
     const char* kg = reinterpret_cast<const char*>(Kp + (int64_t)u * npad * D);
     const char* vg = reinterpret_cast<const char*>(VTp + (int64_t)u * npad * D);
-    constexpr int TILE_BYTES = kBN * D * C::E;
+    char* const Kb0 = smem;
+    char* const Vb0 = smem + 2 * C::TILE_BYTES;
+    const int sw = i & 7;
+    int koff[C::NLD], voff[C::NLD];
+    lds_fill_offsets<C::KRB, C::NLD>(w, lane, koff);
+    lds_fill_offsets<C::VRB, C::NLD>(w, lane, voff);
 
-    uintx4 kr[C::CPT], vr[C::CPT];
-    load_tile<T, D>(kg, vg, tid, kr, vr);
-    for (int t = 0; t < ntiles; ++t) {
-        char* ks = smem + (t & 1) * (C::K_TILE + C::V_TILE);
-        char* vs = ks + C::K_TILE;
-        stage_tile<T, D>(ks, vs, tid, kr, vr);
+    // Software pipeline over key tiles.  While tile t is in its softmax (vector ALU) and P.V (matrix)
+    // stages, the S^T product of tile t+1 already runs on the matrix cores and the loads of K tile t+2
+    // and V^T tile t+1 are in flight straight into LDS.  One barrier per tile.
+    tile_to_lds<T, D>(kg, Kb0, w, koff);
+    tile_to_lds<T, D>(vg, Vb0, w, voff);
+    if (ntiles > 1) tile_to_lds<T, D>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    floatx16 sa[2], sb[2];
+    qk_tile<T, D>(Kb0, i, h, sw, qf, sa);                   // tile 0 is visible to every row
+
+    auto step = [&](int t, floatx16 (&sc)[2], floatx16 (&sn)[2]) {
+        if (t + 2 < ntiles) tile_to_lds<T, D>(kg + (int64_t)(t + 2) * C::TILE_BYTES, Kb0 + (t & 1) * C::TILE_BYTES, w, koff);
+        if (t + 1 < ntiles) tile_to_lds<T, D>(vg + (int64_t)(t + 1) * C::TILE_BYTES, Vb0 + ((t + 1) & 1) * C::TILE_BYTES, w, voff);
+        if (t < my_tiles) {
+            const int t0 = t * kBN;
+            const char* kb = Kb0 + ((t + 1) & 1) * C::TILE_BYTES;
+            const char* vb = Vb0 + (t & 1) * C::TILE_BYTES;
+            if (t0 + kBN - 1 > wave_first_row) {             // tile touches the diagonal (wave-uniform)
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (t0 + 32 * blk + acc_row(r, h) > qrow) sc[blk][r] = -INFINITY;
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[blk][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // raw-logit maximum; the softmax scale (c > 0, log2 domain) is folded into the exponent
+            const float m_new = fmaxf(m_run, mx);            // finite: key 0 is visible to every row
+            const float mc = m_new * c;
+            if (__any(m_new != m_run)) {                     // rescale only when some row's maximum moved
+                const float alpha = fast_exp2(m_run * c - mc);
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < C::ODB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+                m_run = m_new;
+            }
+            float sum = 0.f;
+            if (t + 1 < my_tiles) {
+                // matrix stream: S^T of tile t+1, then P.V of tile t; vector stream: exponentials of tile t
+                qk_tile<T, D>(kb, i, h, sw, qf, sn);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { sc[0][r] = fast_exp2(fmaf(sc[0][r], c, -mc)); sum += sc[0][r]; }
+                PV<T, D>::template run<0>(vb, i, h, sw, sc[0], o);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { sc[1][r] = fast_exp2(fmaf(sc[1][r], c, -mc)); sum += sc[1][r]; }
+                PV<T, D>::template run<1>(vb, i, h, sw, sc[1], o);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { sc[0][r] = fast_exp2(fmaf(sc[0][r], c, -mc)); sum += sc[0][r]; }
+                PV<T, D>::template run<0>(vb, i, h, sw, sc[0], o);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { sc[1][r] = fast_exp2(fmaf(sc[1][r], c, -mc)); sum += sc[1][r]; }
+                PV<T, D>::template run<1>(vb, i, h, sw, sc[1], o);
+            }
+            l_run += sum;
+        }
+        __builtin_amdgcn_s_waitcnt(0);                       // this wave's direct-to-LDS loads have landed
         __syncthreads();
-        if (t + 1 < ntiles)
-            load_tile<T, D>(kg + (int64_t)(t + 1) * TILE_BYTES, vg + (int64_t)(t + 1) * TILE_BYTES, tid, kr, vr);
-        const int t0 = t * kBN;
-        if (t0 > wave_last_row) continue;                    // whole tile is in this wave's future
-
-        // S^T block blk: keys t0 + 32*blk + acc_row(r, h), query column = this lane's
-        float p[2][16];
-        float mx = -INFINITY;
-        {
-            // all K fragments of the tile are requested before the first matrix op, so that the LDS
-            // latency is paid once per tile and not once per fragment
-            uintx4 kf[2][C::CH];
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                for (int cc = 0; cc < C::CH; ++cc)
-                    kf[blk][cc] = *reinterpret_cast<const uintx4*>(ks + (blk * 32 + i) * C::KS + cc * 32 + h * 16);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk) {
-                floatx16 acc = {0};
-#pragma unroll
-                for (int cc = 0; cc < C::CH; ++cc) acc = mma_frag<T>(kf[blk][cc], qf[cc], acc);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) p[blk][r] = acc[r];
-            }
-        }
-        // the first half of the V^T fragments is requested now and lands while the softmax runs
-        uintx4 vf0[C::NVF], vf1[C::NVF];
-        PV<T, D>::template load<0>(vs, i, h, vf0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (t0 + kBN - 1 > wave_first_row) {                 // tile touches the diagonal (wave-uniform)
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (t0 + 32 * blk + acc_row(r, h) > qrow) p[blk][r] = -INFINITY;
-        }
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, p[blk][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // raw-logit maximum; the softmax scale (c > 0, log2 domain) is folded into the exponent
-        const float m_new = fmaxf(m_run, mx);                // finite: key 0 is visible to every row
-        const float mc = m_new * c;
-        float sum = 0.f;
-#pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                p[blk][r] = fast_exp2(fmaf(p[blk][r], c, -mc));
-                sum += p[blk][r];
-            }
-        if (__any(m_new != m_run)) {                         // rescale only when some row's maximum moved
-            const float alpha = fast_exp2(m_run * c - mc);
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < C::ODB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-            m_run = m_new;
-        }
-        l_run += sum;
-        __builtin_amdgcn_sched_barrier(0);
-        PV<T, D>::template load<1>(vs, i, h, vf1);           // lands under the matrix ops of the first half
-        PV<T, D>::run(vf0, p[0], o);
-        PV<T, D>::run(vf1, p[1], o);
+    };
+    for (int t = 0; t < ntiles; t += 2) {
+        step(t, sa, sb);
+        if (t + 1 < ntiles) step(t + 1, sb, sa);
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
