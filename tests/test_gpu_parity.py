@@ -243,7 +243,7 @@ def test_attention_on_already_compacted_cache():
 # ------------------------------------------------------------------ whole layer
 def _layer_parity(w, tau, sample_rows=None, heads=None):
     spec = w.spec
-    B, Hq, Hkv, n, d, dtype = spec.B if w.Q.shape[0] == spec.B else w.Q.shape[0], spec.Hq, spec.Hkv, spec.n, spec.d, spec.dtype
+    B, Hq, Hkv, n, d, dtype = w.Q.shape[0], spec.Hq, spec.Hkv, spec.n, spec.d, spec.dtype
     G = Hq // Hkv
     Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
     mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
@@ -330,6 +330,44 @@ def test_layer_cfg4_headline_shape_sampled():
     say("layer cfg4 (bf16 GQA 28/4, n=18432), sampled output rows")
     w = make_workload(4)
     _layer_parity(w, w.tau, sample_rows=12, heads=[0, 6, 27])
+
+
+def test_layer_cfg5_first_and_last_layer_then_decode_on_evicted_cache():
+    say("layer cfg5 (bf16, 32 heads, n=8192), layers 0 and 31, batch slice of 1; then decode on the evicted cache")
+    fracs = []
+    for layer in (0, 31):
+        w = make_workload(5, layer=layer, batch=1)
+        kept = _layer_parity(w, w.tau, sample_rows=6, heads=[3, 30])
+        fracs.append(np.mean(kept))
+    assert abs(fracs[0] - fracs[1]) > 0.05         # the spike ramp makes the kept ratio layer dependent
+    # decode: two steps against the evicted cache of the last layer
+    spec = w.spec
+    Q, K, V = dev(w.Q, "bf16"), dev(w.K, "bf16"), dev(w.V, "bf16")
+    mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
+    idx, k = z.zipvl_select(mass, rank, w.tau)
+    cap = int(k.max().item()) + 4
+    Kc, Vc, ln = z.zipvl_compact_kv(K, V, idx, k, cap)
+    r = np.random.Generator(np.random.PCG64(5))
+    from workloads import round_to_bf16
+    H, d = spec.Hq, spec.d
+    idx_h, k_h = idx.cpu().numpy(), k.cpu().numpy()
+    Kh = [w.K[0, g][idx_h[g, :k_h[g]]] for g in range(H)]
+    Vh = [w.V[0, g][idx_h[g, :k_h[g]]] for g in range(H)]
+    for step in range(2):
+        q = round_to_bf16(r.standard_normal((H, d)).astype(np.float32))
+        kn = round_to_bf16(r.standard_normal((H, d)).astype(np.float32))
+        vn = round_to_bf16(r.standard_normal((H, d)).astype(np.float32))
+        z.zipvl_kv_append(Kc, Vc, ln, dev(kn, "bf16"), dev(vn, "bf16"), B=1, Hkv=H)
+        o = z.zipvl_decode_attn(dev(q, "bf16"), Kc, Vc, ln, w.scale, B=1, Hq=H, Hkv=H)
+        torch.cuda.synchronize()
+        oh = host64(o)
+        for g in (0, 17, 31):
+            ref, Kh[g], Vh[g], _ = oz.decode_step(q[g], kn[g], vn[g], Kh[g], Vh[g], len(Kh[g]), w.scale)
+            assert np.abs(oh[g] - ref).max() <= 2e-2
+        for g in range(H):
+            if g not in (0, 17, 31):
+                Kh[g] = np.concatenate([Kh[g], kn[g][None]]); Vh[g] = np.concatenate([Vh[g], vn[g][None]])
+    assert ln.cpu().tolist() == [int(x) + 2 for x in k_h]
 
 
 # ------------------------------------------------------------------ decode

@@ -170,3 +170,31 @@ def make_custom(B: int, Hq: int, Hkv: int, n: int, d: int, dtype: str = "f32", *
         probe_pos = np.arange(n - mm, n, dtype=np.int32)
     probe_pos = np.ascontiguousarray(probe_pos, dtype=np.int32)
     return Workload(spec, seed, 0, gamma, Q, K, V, probe_pos, 1.0 / float(np.sqrt(d)), spikes)
+
+
+def make_stack_layer_device(layer: int, device: str = "cuda:0", gamma: float = GAMMA_DEFAULT,
+                            batch: Optional[int] = None):
+    """One layer of the 32-layer stack (shape 5) drawn on the GPU with torch's seeded generator
+    (the host generator needs ~5 s per layer; 32 layers are 25.8 GB).  Same recipe as `_draw`;
+    the spike set of a (batch, head) unit is the `cnt` positions with the largest of n uniform
+    draws.  Returns bf16 tensors Q, K, V [B,H,n,d] and the probe positions."""
+    import torch
+    spec = CONFIGS[5]
+    B = spec.B if batch is None else batch
+    H, n, d = spec.Hq, spec.n, spec.d
+    gen = torch.Generator(device=device)
+    gen.manual_seed(base_seed(5, layer))
+    u = torch.randn((B, H, 1, d), generator=gen, device=device, dtype=torch.float32)
+    u = u / u.norm(dim=-1, keepdim=True)
+    K = torch.randn((B, H, n, d), generator=gen, device=device, dtype=torch.float32)
+    V = torch.randn((B, H, n, d), generator=gen, device=device, dtype=torch.float32)
+    cnt = int(round((0.30 - 0.28 * layer / 31.0) * n))
+    pos = torch.rand((B, H, n), generator=gen, device=device).topk(cnt, dim=-1).indices
+    spike = torch.zeros((B, H, n, 1), device=device, dtype=torch.float32)
+    spike.scatter_(2, pos.unsqueeze(-1), float(spec.spike))
+    K += spike * u
+    Q = torch.randn((B, H, n, d), generator=gen, device=device, dtype=torch.float32)
+    Q += float(gamma * np.sqrt(d)) * u
+    m = min(M_PROBE, n)
+    probe = np.arange(n - m, n, dtype=np.int32)
+    return (Q.to(torch.bfloat16), K.to(torch.bfloat16), V.to(torch.bfloat16), probe, 1.0 / float(np.sqrt(d)))
