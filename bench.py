@@ -108,6 +108,7 @@ def run_stack(args):
     Kt = torch.empty((units, n, d), dtype=torch.bfloat16, device=dev)
     Vt = torch.empty_like(Kt)
     lt = torch.empty((units,), dtype=torch.int32, device=dev)
+    Kt4, Vt4 = Kt.view(B, H, n, d), Vt.view(B, H, n, d)
     ws_s = ws_p = None
     caches, fulls, kept, layer_ms = [], [], [], []
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -123,7 +124,7 @@ def run_stack(args):
             z.zipvl_score(Q, K, probe, scale, mass=mass, rank=rank, ws=ws_s)
             z.zipvl_select(mass, rank, tau, idx=idx, k=k)
             z.zipvl_compact_kv(K, V, idx, k, n, Kc=Kt, Vc=Vt, length=lt)
-            z.zipvl_sparse_prefill(Q, K, V, idx, k, scale, z.OUT_FULL, O=O, ws=ws_p)
+            z.zipvl_sparse_prefill(Q, Kt4, Vt4, idx, k, scale, z.OUT_FULL | z.KV_ALREADY_COMPACT, O=O, ws=ws_p)
         one_layer()                                   # warm-up of this layer's shapes
         torch.cuda.synchronize()
         ev0.record()
@@ -240,6 +241,7 @@ def main():
     k = torch.empty((units,), dtype=torch.int32, device=dev)
     Kc = torch.empty((units, n, d), dtype=tdt, device=dev)
     Vc = torch.empty_like(Kc)
+    Kc4, Vc4 = Kc.view(B, Hkv, n, d), Vc.view(B, Hkv, n, d)     # the evicted cache, as the attention call takes it
     ln = torch.empty((units,), dtype=torch.int32, device=dev)
     O = torch.empty((B, Hq, n, d), dtype=tdt, device=dev)
     ws_s = torch.empty(max(256, z.workspace_bytes(z.OP_SCORE, dm, len(w.probe_pos))), dtype=torch.uint8, device=dev)
@@ -249,7 +251,7 @@ def main():
         z.zipvl_score(Q, K, w.probe_pos, w.scale, mass=mass, rank=rank, ws=ws_s)
         z.zipvl_select(mass, rank, tau, idx=idx, k=k)
         z.zipvl_compact_kv(K, V, idx, k, n, Kc=Kc, Vc=Vc, length=ln)
-        z.zipvl_sparse_prefill(Q, K, V, idx, k, w.scale, z.OUT_FULL, O=O, ws=ws_p)
+        z.zipvl_sparse_prefill(Q, Kc4, Vc4, idx, k, w.scale, z.OUT_FULL | z.KV_ALREADY_COMPACT, O=O, ws=ws_p)
 
     for _ in range(args.warmup):
         step()

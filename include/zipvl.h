@@ -99,8 +99,9 @@ int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims,
  * sorted accumulated scores reach tau of the total) and Eq. (9) (that many
  * tokens with the largest normalised score); Algorithm 1, steps 3-5.
  *
- * Per unit u (row u of mass/rank, n entries each, finite and >= 0, sum < 4096; an entry with the
- * sign bit set is ordered and summed as 0):
+ * Per unit u (row u of mass/rank, n entries each, finite and >= 0, mass summing to less than 2 - it
+ * sums to 1 when it comes from zipvl_score; an entry with the sign bit set is ordered and summed as 0;
+ * n < 2^23):
  *   q_j = floor(mass_j * 2^40)  (exact integers; the sums below are integer sums)
  *   k   = n if tau >= 1, else max(1, min{ i : sum of the i largest q >= ceil(tau * sum of all q) })
  *   T   = the k tokens with the largest rank (equal values: lower index first)

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
     const T* __restrict__ K, const T* __restrict__ V,
     int64_t ks0, int64_t ks1, int64_t ks2, int64_t vs0, int64_t vs1, int64_t vs2,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
-    T* __restrict__ Kp, T* __restrict__ VTp, int n, int npad, int Hkv, int rows_are_kept)
+    T* __restrict__ Kp, T* __restrict__ VTp, int n, int npad, int Hkv, int rows_are_kept, int skip_k)
 {
     constexpr int EPF = Elem<T>::kPerFrag;
     constexpr int CPR = D / EPF;
@@ -78,10 +78,10 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
         uintx4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
         if (row < kk) {
             const int src = (idx && !rows_are_kept) ? idx[(int64_t)u * n + row] : row;
-            kv = load16(Kb + (int64_t)src * ks2 + cc * EPF);
+            if (!skip_k) kv = load16(Kb + (int64_t)src * ks2 + cc * EPF);
             vv = load16(Vb + (int64_t)src * vs2 + cc * EPF);
         }
-        store16(Kp + ((int64_t)u * npad + row) * D + cc * EPF, kv);
+        if (!skip_k) store16(Kp + ((int64_t)u * npad + row) * D + cc * EPF, kv);
         store16(tile + r * LS + cc * EPF, vv);
     }
     __syncthreads();
@@ -205,7 +205,7 @@ template <> __device__ __forceinline__ void store_out4<__bf16>(__bf16* dst, floa
 template <typename T, int D>
 __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_kernel(
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
-    const T* __restrict__ Kp, const T* __restrict__ VTp,
+    const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ VTp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
     T* __restrict__ O, int n, int npad, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped)
 {
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
     const int ntiles = (min(i0 + kBM, kk) + kBN - 1) / kBN;
     const int wave_first_row = i0 + 32 * w, wave_last_row = wave_first_row + 31;
     const int my_tiles = min(ntiles, wave_last_row / kBN + 1);   // later tiles lie wholly in this wave's future
-    const char* kg = reinterpret_cast<const char*>(Kp + (int64_t)u * npad * D);
+    const char* kg = reinterpret_cast<const char*>(Kp + b * kp0 + g * kp1);   // row-major kept K rows of this unit
     const char* vg = reinterpret_cast<const char*>(VTp + (int64_t)u * npad * D);
     char* const Kb0 = smem;
     char* const Vb0 = smem + 2 * C::TILE_BYTES;
@@ -378,11 +378,14 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     const int out_compact = (flags & ZIPVL_OUT_COMPACT) ? 1 : 0;
     const int rows_are_kept = (flags & ZIPVL_KV_ALREADY_COMPACT) ? 1 : 0;
 
+    // An evicted cache with contiguous rows and whole 64-row tiles is read in place: only V is repacked.
+    // (Rows between k and the end of the last tile may hold anything: they are masked, never summed.)
+    const int skip_k = (rows_are_kept && d.k_strides[2] == D && d.n % kBN == 0) ? 1 : 0;
     {
         KernelTimer tm(ZIPVL_K_PACK_KV, st);
         hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kBN, units), dim3(256), 0, st,
             (const T*)K, (const T*)V, d.k_strides[0], d.k_strides[1], d.k_strides[2],
-            d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept);
+            d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept, skip_k);
     }
     int rc = check_launch("pack_kv");
     if (rc) return rc;
@@ -401,7 +404,8 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
         if (blocks > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
         hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((unsigned)blocks), dim3(256),
             C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-            (const T*)Kp, (const T*)VTp, idx, k, (T*)O, d.n, npad, BH, d.Hq, d.Hkv, scale * kLog2e,
+            skip_k ? (const T*)K : (const T*)Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
+            skip_k ? d.k_strides[1] : (int64_t)npad * D, (const T*)VTp, idx, k, (T*)O, d.n, npad, BH, d.Hq, d.Hkv, scale * kLog2e,
             out_compact, (!out_compact && idx) ? 1 : 0);
     }
     return check_launch("flash_kept");

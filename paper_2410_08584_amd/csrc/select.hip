@@ -28,8 +28,6 @@ constexpr int kRep = 16;              // histogram replicas (lane % 16) against 
 struct SelShared {
     uint32_t cnt[256 * kRep];
     unsigned long long sum[256 * kRep];
-    uint32_t bin_cnt[256];
-    unsigned long long bin_sum[256];
     unsigned long long target;
     unsigned long long base_sum;
     uint32_t base_cnt;
@@ -88,9 +86,12 @@ __device__ __forceinline__ unsigned long long fixed40_of_key(uint32_t key) {
 
 // One descent over the 31 key bits in four digits, exponent byte first (8 + 8 + 8 + 7 bits).  The
 // first digit sees every element and uses kRep histogram replicas; later digits only see the
-// elements that share the prefix and use one.  WITH_SUM: cross on the integer sum
-// (target = sh.target, fixed after the first digit from the grand total);
-// otherwise cross on the element count (target = cnt_target).
+// elements that share the prefix and use one.  WITH_SUM: a histogram slot packs the element count
+// (bits 41..63) over the integer score sum (bits 0..40, sum of a unit < 2^41), one LDS atomic per
+// element, and the descent crosses on the sum (target fixed after the first digit from the grand
+// total); otherwise slots are plain counts and the descent crosses on cnt_target.
+constexpr int kSumBits = 41;
+
 template <bool WITH_SUM>
 __device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
                               SelShared& sh, uint32_t& prefix_out, uint32_t& base_cnt_out,
@@ -105,46 +106,44 @@ __device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
         const uint32_t dmask = pass < 3 ? 255u : 127u;
         const int rep = pass == 0 ? kRep : 1;
         for (int i = tid; i < 256 * rep; i += kSelThreads) {
-            sh.cnt[i] = 0;
-            if (WITH_SUM) sh.sum[i] = 0;
+            if (WITH_SUM) sh.sum[i] = 0; else sh.cnt[i] = 0;
         }
         __syncthreads();
         keys.for_each([&](int, uint32_t key) {
             if ((key & mask) == prefix) {
                 const int slot = ((key >> shift) & dmask) * rep + (tid & (rep - 1));
-                atomicAdd(&sh.cnt[slot], 1u);
-                if (WITH_SUM) atomicAdd(&sh.sum[slot], fixed40_of_key(key));
+                if (WITH_SUM) atomicAdd(&sh.sum[slot], (1ull << kSumBits) + fixed40_of_key(key));
+                else atomicAdd(&sh.cnt[slot], 1u);
             }
         });
         __syncthreads();
-        if (tid < 256) {
-            uint32_t c = 0;
-            unsigned long long s = 0;
-            for (int r = 0; r < rep; ++r) {
-                c += sh.cnt[tid * rep + r];
-                if (WITH_SUM) s += sh.sum[tid * rep + r];
-            }
-            sh.bin_cnt[tid] = c;
-            sh.bin_sum[tid] = s;
-        }
-        __syncthreads();
         if (tid < 64) {
-            // lane l scans bins 255-4l .. 252-4l (descending value order)
+            // lane l owns bins 255-4l .. 252-4l (descending value order): fold the replicas, then scan
             uint32_t c[4], lc = 0;
             unsigned long long s[4], ls = 0;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                c[t] = sh.bin_cnt[255 - (4 * tid + t)];
-                s[t] = WITH_SUM ? sh.bin_sum[255 - (4 * tid + t)] : 0ull;
-                lc += c[t];
-                ls += s[t];
+                const int bin = 255 - (4 * tid + t);
+                uint32_t cc = 0;
+                unsigned long long ss = 0;
+                for (int r = 0; r < rep; ++r) {
+                    if (WITH_SUM) {
+                        const unsigned long long v = sh.sum[bin * rep + r];
+                        cc += (uint32_t)(v >> kSumBits);
+                        ss += v & ((1ull << kSumBits) - 1ull);
+                    } else {
+                        cc += sh.cnt[bin * rep + r];
+                    }
+                }
+                c[t] = cc; s[t] = ss;
+                lc += cc; ls += ss;
             }
             uint32_t ic = lc;
             unsigned long long is = ls;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const uint32_t tc = __shfl_up(ic, o);
-                const unsigned long long ts = __shfl_up(is, o);
+                const unsigned long long ts = WITH_SUM ? __shfl_up(is, o) : 0ull;
                 if (tid >= o) { ic += tc; is += ts; }
             }
             unsigned long long target;
@@ -278,7 +277,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
 }
 
-constexpr int kSelMaxLdsKeys = 26624;      // 104 KiB of keys beside the 52 KiB of histograms
+constexpr int kSelMaxLdsKeys = 27648;      // 108 KiB of keys beside the 48 KiB of histograms
 
 int launch_select(const float* mass, const float* rank, int units, int n, double tau,
                   int32_t* idx, int32_t* k, hipStream_t st)

@@ -145,7 +145,7 @@ int zipvl_select(const float* mass, const float* rank, int units, int n, double 
     (void)ws; (void)ws_bytes;
     if (!mass || !idx || !k) return set_error(ZIPVL_EINVAL, "%s: mass, idx and k must not be NULL", fn);
     if (units < 1 || n < 1) return set_error(ZIPVL_EINVAL, "%s: units and n must be positive (got %d, %d)", fn, units, n);
-    if (n > (1 << 24)) return set_error(ZIPVL_ESHAPE, "%s: n = %d exceeds 2^24", fn, n);
+    if (n >= (1 << 23)) return set_error(ZIPVL_ESHAPE, "%s: n = %d must be below 2^23", fn, n);
     if (!(tau > 0.0) || !(tau <= 1.0)) return set_error(ZIPVL_EINVAL, "%s: tau = %g is outside (0, 1]", fn, tau);
     if ((reinterpret_cast<uintptr_t>(mass) | reinterpret_cast<uintptr_t>(rank) |
          reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(k)) & 3u)

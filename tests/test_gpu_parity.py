@@ -221,9 +221,11 @@ def test_attention_compact_output_rows():
     _attention_case(1, 4, 2, 500, 128, "bf16", [333, 128], seed=7, flags=z.OUT_COMPACT)
 
 
-def test_attention_on_already_compacted_cache():
-    say("attention KV_ALREADY_COMPACT")
-    B, Hq, Hkv, n, d, dtype = 1, 4, 2, 400, 128, "bf16"
+@pytest.mark.parametrize("n", [400, 448])
+def test_attention_on_already_compacted_cache(n):
+    # n = 448 (whole 64-row tiles, contiguous rows) reads the evicted K cache in place; n = 400 repacks it
+    say(f"attention KV_ALREADY_COMPACT n={n}")
+    B, Hq, Hkv, d, dtype = 1, 4, 2, 128, "bf16"
     w = make_custom(B, Hq, Hkv, n, d, dtype, seed=8)
     Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
     ks = [211, 77]
@@ -232,11 +234,14 @@ def test_attention_on_already_compacted_cache():
     for u in range(2):
         idx[u, :ks[u]] = np.sort(r.choice(n, ks[u], replace=False))
     idx_d, k_d = torch.from_numpy(idx).to(DEV), torch.tensor(ks, dtype=torch.int32, device=DEV)
-    Kc, Vc, _ = z.zipvl_compact_kv(K, V, idx_d, k_d, n)
+    Kc = torch.full((2, n, d), float("nan"), dtype=torch.bfloat16, device=DEV)   # rows beyond k stay NaN
+    Vc = torch.full((2, n, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    z.zipvl_compact_kv(K, V, idx_d, k_d, n, Kc=Kc, Vc=Vc)
     O1 = z.zipvl_sparse_prefill(Q, K, V, idx_d, k_d, w.scale)
     O2 = z.zipvl_sparse_prefill(Q, Kc.view(B, Hkv, n, d), Vc.view(B, Hkv, n, d), idx_d, k_d, w.scale,
                                 z.KV_ALREADY_COMPACT)
     torch.cuda.synchronize()
+    assert not torch.isnan(O2.float()).any()
     assert torch.equal(O1, O2)
 
 
