@@ -201,6 +201,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="shape 5: number of layers (default all 32)")
     ap.add_argument("--decode-steps", type=int, default=256, help="shape 5: decode steps per cache kind")
     ap.add_argument("--gamma", type=float, default=None, help="query-mean strength of the generator (default 1.75)")
+    ap.add_argument("--probes", choices=["recent", "hybrid"], default="recent",
+                    help="probe rows: the last 64 positions (benchmark configs) or the paper's 64 recent + 64 random")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -228,6 +230,9 @@ def main():
     dev = "cuda:0"
     gamma = GAMMA_DEFAULT if args.gamma is None else args.gamma
     w = make_workload(args.workload, gamma=gamma)
+    if args.probes == "hybrid":
+        from workloads import hybrid_probes
+        w.probe_pos = hybrid_probes(w.spec.n, seed=w.seed)
     spec, tau = w.spec, w.tau
     B, Hq, Hkv, n, d = spec.B, spec.Hq, spec.Hkv, spec.n, spec.d
     tdt = torch.bfloat16 if spec.dtype == "bf16" else torch.float32
@@ -322,7 +327,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "B": B, "Hq": Hq, "Hkv": Hkv, "n": n, "d": d, "tau": tau,
-                   "probes": f"last {len(w.probe_pos)}", "gamma": gamma, "seed": w.seed},
+                   "probes": f"last {len(w.probe_pos)}" if args.probes == "recent" else "64 recent + 64 random", "gamma": gamma, "seed": w.seed},
         "kept_pct": 100.0 * float(r.mean()), "kept_sq_pct": 100.0 * float((r * r).mean()),
         "k_per_unit": [int(x) for x in k_h[:16]],
         "kernels": kern,

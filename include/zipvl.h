@@ -45,7 +45,7 @@ extern "C" {
 #define ZIPVL_F32   0
 #define ZIPVL_BF16  1
 
-#define ZIPVL_MAX_PROBES 64
+#define ZIPVL_MAX_PROBES 128
 
 /* ops for zipvl_workspace_bytes */
 #define ZIPVL_OP_SCORE          1

@@ -18,15 +18,16 @@
 
 namespace zipvl {
 
-constexpr int kNB = ZIPVL_MAX_PROBES / 32;   // probe blocks of 32 (rows beyond m are masked out)
-constexpr int kProbes = kNB * 32;
+// Probe rows are handled in blocks of 32 (NB = 2 for m <= 64, NB = 4 for m <= 128; rows beyond m are masked out).
+constexpr int kMaxNB = ZIPVL_MAX_PROBES / 32;
 constexpr int kMaxGroup = 16;
 constexpr int kScoreWaves = 4;
 constexpr int kScoreThreads = 64 * kScoreWaves;
 constexpr int kScoreKeys = 32 * kScoreWaves;  // keys per workgroup
 
-template <typename T, int D>
+template <typename T, int D, int NB = 2>
 struct ScoreCfg {
+    static constexpr int kProbes = NB * 32;
     static constexpr int E = Elem<T>::kBytes;
     static constexpr int CH = D / Elem<T>::kPerChunk;      // fragments per row per lane
     static constexpr int QS = D * E + 16;                   // padded LDS row of a probe query (bytes)
@@ -44,15 +45,16 @@ __device__ __forceinline__ void load_row_frags(const T* row, int h, uintx4 (&f)[
 
 // PASS 1: partial[(bh * nsplit + split) * 64 + probe] = (raw-logit maximum, sum of exp2((s - max) * c))
 // PASS 2: mass / rank of the workgroup's keys, from bias[bh * 64 + probe] = max * c + log2(sum)
-template <typename T, int D, int PASS>
+template <typename T, int D, int PASS, int NB>
 __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
     const T* __restrict__ Q, const T* __restrict__ K,
     int64_t qs0, int64_t qs1, int64_t qs2, int64_t ks0, int64_t ks1, int64_t ks2,
     ProbeList probes, int m, int n, int n_eff, float c, float2* __restrict__ partial, int nsplit,
     const float* __restrict__ bias, float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv)
 {
-    using C = ScoreCfg<T, D>;
+    using C = ScoreCfg<T, D, NB>;
     constexpr int CH = C::CH;
+    constexpr int kProbes = NB * 32, kNB = NB;
     extern __shared__ __attribute__((aligned(16))) char smem[];     // [gc][64] padded probe rows
     __shared__ int sp[kProbes];
     __shared__ __attribute__((aligned(16))) float row_bias[kMaxGroup][kProbes];
@@ -216,20 +218,20 @@ __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
 
 // Merge the per-slice statistics of every (head, probe row) into one exponent offset
 // bias = max * c + log2(sum), so that exp2(s * c - bias) is the normalised probability.
-// Block = 64 probe rows x 8 slice groups.
-__global__ __launch_bounds__(512) void score_rowfinal_kernel(
-    const float2* __restrict__ partial, int nsplit, int m, float c, float* __restrict__ bias)
+// Block = np probe rows x 8 slice groups.
+__global__ __launch_bounds__(1024) void score_rowfinal_kernel(
+    const float2* __restrict__ partial, int nsplit, int m, int np, float c, float* __restrict__ bias)
 {
-    __shared__ float2 red[8][kProbes];
-    const int bh = blockIdx.x, pc = threadIdx.x & 63, sg = threadIdx.x >> 6;
-    const float2* p = partial + (int64_t)bh * nsplit * kProbes + pc;
+    __shared__ float2 red[8][ZIPVL_MAX_PROBES];
+    const int bh = blockIdx.x, pc = threadIdx.x % np, sg = threadIdx.x / np;
+    const float2* p = partial + (int64_t)bh * nsplit * np + pc;
     float M = -INFINITY, L = 0.f;
     for (int s0 = sg; s0 < nsplit; s0 += 32) {              // 4 independent loads per round
         float2 v[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int s = s0 + 8 * q;
-            v[q] = s < nsplit ? p[(int64_t)s * kProbes] : make_float2(-INFINITY, 0.f);
+            v[q] = s < nsplit ? p[(int64_t)s * np] : make_float2(-INFINITY, 0.f);
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -249,40 +251,39 @@ __global__ __launch_bounds__(512) void score_rowfinal_kernel(
 #pragma unroll
             for (int q = 0; q < 8; ++q) Lt += red[q][pc].y * fast_exp2((red[q][pc].x - Mt) * c);
         }
-        bias[(int64_t)bh * kProbes + pc] = (pc < m && Lt > 0.f) ? Mt * c + __log2f(Lt) : INFINITY;
+        bias[(int64_t)bh * np + pc] = (pc < m && Lt > 0.f) ? Mt * c + __log2f(Lt) : INFINITY;
     }
 }
 
 // ---------------------------------------------------------------- host side
 static int score_splits(const zipvl_dims& d) { return (d.n + kScoreKeys - 1) / kScoreKeys; }
+static int probe_rows(int m) { return m <= 64 ? 64 : 128; }
 
-static size_t score_partial_bytes(const zipvl_dims& d) {
-    return (size_t)d.B * d.Hq * score_splits(d) * kProbes * sizeof(float2);
+static size_t score_partial_bytes(const zipvl_dims& d, int m) {
+    return (size_t)d.B * d.Hq * score_splits(d) * probe_rows(m) * sizeof(float2);
 }
 
 size_t score_workspace_bytes(const zipvl_dims& d, int m) {
-    (void)m;
-    return score_partial_bytes(d) + (size_t)d.B * d.Hq * kProbes * sizeof(float);
+    return score_partial_bytes(d, m) + (size_t)d.B * d.Hq * probe_rows(m) * sizeof(float);
 }
 
-template <typename T, int D>
+template <typename T, int D, int NB>
 static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
                           int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
 {
-    using C = ScoreCfg<T, D>;
+    using C = ScoreCfg<T, D, NB>;
     const float c = scale * kLog2e;
     float2* partial = (float2*)ws;
-    float* bias = (float*)((char*)ws + score_partial_bytes(d));
-    const int G = d.Hq / d.Hkv, units = d.B * d.Hkv;
+    float* bias = (float*)((char*)ws + score_partial_bytes(d, m));
+    const int units = d.B * d.Hkv;
     // probe rows of GC heads, then the per-wave statistics of pass 1
-    const size_t lds = (size_t)C::GC * C::HEAD_BYTES + (size_t)kScoreWaves * C::GC * kNB * 64 * sizeof(float2);
-    (void)G;
+    const size_t lds = (size_t)C::GC * C::HEAD_BYTES + (size_t)kScoreWaves * C::GC * NB * 64 * sizeof(float2);
     static bool attr_done = false;
     if (!attr_done) {
-        const int cap = 64 * 1024;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 1>),
+        const int cap = 96 * 1024;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 1, NB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 2>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 2, NB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
             return set_error(ZIPVL_EHIP, "score: cannot reserve LDS for the probe rows");
         attr_done = true;
@@ -290,7 +291,7 @@ static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, con
     const int nsplit = (n_eff + kScoreKeys - 1) / kScoreKeys;
     {
         KernelTimer tm(ZIPVL_K_SCORE_ROWSTATS, st);
-        hipLaunchKernelGGL((score_pass_kernel<T, D, 1>), dim3(nsplit, units), dim3(kScoreThreads), lds, st,
+        hipLaunchKernelGGL((score_pass_kernel<T, D, 1, NB>), dim3(nsplit, units), dim3(kScoreThreads), lds, st,
             (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, partial, nsplit,
             (const float*)nullptr, (float*)nullptr, (float*)nullptr, d.Hq, d.Hkv);
@@ -299,17 +300,25 @@ static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, con
     if (rc) return rc;
     {
         KernelTimer tm(ZIPVL_K_SCORE_ROWFINAL, st);
-        hipLaunchKernelGGL(score_rowfinal_kernel, dim3(d.B * d.Hq), dim3(512), 0, st,
-            (const float2*)partial, nsplit, m, c, bias);
+        hipLaunchKernelGGL(score_rowfinal_kernel, dim3(d.B * d.Hq), dim3(NB * 32 * 8), 0, st,
+            (const float2*)partial, nsplit, m, NB * 32, c, bias);
     }
     rc = check_launch("score_rowfinal");
     if (rc) return rc;
     KernelTimer tm(ZIPVL_K_SCORE_COLSUM, st);
-    hipLaunchKernelGGL((score_pass_kernel<T, D, 2>), dim3(score_splits(d), units), dim3(kScoreThreads), lds, st,
+    hipLaunchKernelGGL((score_pass_kernel<T, D, 2, NB>), dim3(score_splits(d), units), dim3(kScoreThreads), lds, st,
         (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
         d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, (float2*)nullptr, nsplit,
         (const float*)bias, mass, rank, d.Hq, d.Hkv);
     return check_launch("score_colsum");
+}
+
+template <typename T, int D>
+static int launch_score_nb(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
+                           int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
+{
+    if (m <= 64) return launch_score_t<T, D, 2>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    return launch_score_t<T, D, 4>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
 }
 
 int launch_score(const void* Q, const void* K, const zipvl_dims& d, const int32_t* probe_pos, int m,
@@ -320,11 +329,11 @@ int launch_score(const void* Q, const void* K, const zipvl_dims& d, const int32_
     for (int t = 0; t < ZIPVL_MAX_PROBES; ++t) pl.pos[t] = t < m ? probe_pos[t] : -1;
     const int n_eff = probe_pos[m - 1] + 1;
     if (d.dtype == ZIPVL_BF16) {
-        if (d.d == 128) return launch_score_t<__bf16, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-        return launch_score_t<__bf16, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+        if (d.d == 128) return launch_score_nb<__bf16, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+        return launch_score_nb<__bf16, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
     }
-    if (d.d == 128) return launch_score_t<float, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-    return launch_score_t<float, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    if (d.d == 128) return launch_score_nb<float, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    return launch_score_nb<float, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
 }
 
 }  // namespace zipvl

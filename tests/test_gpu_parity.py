@@ -15,7 +15,7 @@ import torch
 
 import paper_2410_08584_amd as z
 from oracle import zipvl_oracle as oz
-from workloads import make_custom, make_workload
+from workloads import hybrid_probes, make_custom, make_workload
 
 pytestmark = pytest.mark.gpu
 
@@ -132,6 +132,10 @@ SCORE_CASES = [
     (1, 2, 1, 1500, 128, "f32", 64, None),
     (1, 7, 1, 2100, 128, "bf16", 64, "scattered"),
     (1, 2, 2, 70, 64, "f32", 64, None),
+    (1, 4, 2, 1500, 128, "bf16", 128, "hybrid"),
+    (1, 2, 2, 900, 64, "f32", 100, "hybrid"),
+    (1, 3, 1, 640, 64, "bf16", 128, "hybrid"),
+    (1, 2, 1, 700, 128, "f32", 128, "hybrid"),
 ]
 
 
@@ -143,7 +147,10 @@ def test_scores_match_oracle(case):
     if probe == "scattered":
         r = np.random.Generator(np.random.PCG64(3))
         pp = np.sort(np.concatenate([r.choice(n - 200, m - 20, replace=False), np.arange(n - 20, n)])).astype(np.int32)
+    if probe == "hybrid":
+        pp = hybrid_probes(n, seed=n, recent=64, random=m - 64)
     w = make_custom(B, Hq, Hkv, n, d, dtype, seed=100 + n, m=m, probe_pos=pp)
+    assert len(w.probe_pos) == m
     Q, K = dev(w.Q, dtype), dev(w.K, dtype)
     mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
     torch.cuda.synchronize()
@@ -299,6 +306,14 @@ def test_layer_cfg1_full():
     say("layer cfg1 (fp32, n=576)")
     w = make_workload(1)
     _layer_parity(w, w.tau)
+
+
+def test_layer_with_hybrid_probe_set():
+    say("layer with 64 recent + 64 random probes (bf16, GQA 6/2, n=2000)")
+    n = 2000
+    w = make_custom(1, 6, 2, n, 128, "bf16", seed=21, probe_pos=hybrid_probes(n, seed=5))
+    assert len(w.probe_pos) == 128
+    _layer_parity(w, 0.975)
 
 
 def test_layer_tau_one_is_dense_attention():

@@ -68,7 +68,7 @@ def test_score_rejects_bad_arguments(lib):
     assert _score(lib, _dims(), [5, 5, 6]) == -1 and "ascending" in z.zipvl_last_error()
     assert _score(lib, _dims(), [5, 128]) == -1
     assert _score(lib, _dims(), []) == -1
-    assert _score(lib, _dims(), list(range(65))) == -2
+    assert _score(lib, _dims(n=256), list(range(129))) == -2
     assert _score(lib, _dims(), ok, scale=0.0) == -1
     assert _score(lib, _dims(), ok, ws=None) == -4
     assert _score(lib, _dims(), ok, ws_bytes=16) == -4 and "workspace" in z.zipvl_last_error()

@@ -92,6 +92,22 @@ def test_all_rows_probe_equals_dense_softmax_column_sums_torch():
     assert oz.structural_count(n, np.arange(n)).tolist() == list(range(n, 0, -1))
 
 
+def test_scattered_probes_columns_no_probe_sees_get_zero_rank_and_mass_still_sums_to_one():
+    # hybrid-style probe list: scattered rows plus a recent span that stops before the end
+    r = _rng(55)
+    n, d = 120, 8
+    Q, K = r.standard_normal((2, n, d)), r.standard_normal((1, n, d))
+    probe = np.array([7, 30, 31, 64, 100, 101, 102, 103])
+    mass, rank = oz.token_scores(Q, K, probe, 0.3)
+    np.testing.assert_allclose(mass.sum(), 1.0, atol=1e-12)
+    assert np.all(mass[0, 104:] == 0) and np.all(rank[0, 104:] == 0)
+    cnt = oz.structural_count(n, probe)
+    assert cnt[0] == 8 and cnt[8] == 7 and cnt[103] == 1 and cnt[104] == 0
+    # a column only the last probes see is normalised by that smaller count: rank >= mass * m / cnt
+    j = 102
+    np.testing.assert_allclose(rank[0, j], mass[0, j] * len(probe) / cnt[j], rtol=1e-12)
+
+
 def test_group_average_of_query_heads():
     r = _rng(5)
     n, d = 30, 8

@@ -45,3 +45,12 @@ def test_gqa_long_video_spikes_sit_in_four_frame_runs():
     r = np.random.Generator(np.random.PCG64(3))
     S = _spike_set(4, spec, r, 0)
     assert len(S) == 553 and len(np.unique(S // (8 * 144))) <= 4
+
+
+def test_hybrid_probe_set_is_sorted_unique_and_holds_the_recent_span():
+    from workloads import hybrid_probes
+    p = hybrid_probes(3000, seed=1)
+    assert len(p) == 128 and np.all(np.diff(p) > 0)
+    assert p[-64:].tolist() == list(range(3000 - 64, 3000)) and p[63] < 3000 - 64
+    assert hybrid_probes(3000, seed=1).tolist() == p.tolist() and hybrid_probes(3000, seed=2).tolist() != p.tolist()
+    assert hybrid_probes(40, seed=0).tolist() == list(range(40))

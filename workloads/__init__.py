@@ -5,7 +5,7 @@ It holds none of the method's arithmetic and imports neither the CPU oracle
 nor the HIP library; both are fed from here.
 """
 from .generators import (CONFIGS, WorkloadSpec, Workload, make_workload,
-                         make_custom, make_stack_layer_device, round_to_bf16, bf16_bits, base_seed)
+                         make_custom, make_stack_layer_device, hybrid_probes, round_to_bf16, bf16_bits, base_seed)
 
 __all__ = ["CONFIGS", "WorkloadSpec", "Workload", "make_workload",
-           "make_custom", "make_stack_layer_device", "round_to_bf16", "bf16_bits", "base_seed"]
+           "make_custom", "make_stack_layer_device", "hybrid_probes", "round_to_bf16", "bf16_bits", "base_seed"]

@@ -141,6 +141,16 @@ def _draw(spec: WorkloadSpec, rng: np.random.Generator, gamma: float, spike_fn,
     return Q, K, V, spikes
 
 
+def hybrid_probes(n: int, seed: int, recent: int = 64, random: int = 64) -> np.ndarray:
+    """The probe recipe of the paper's supplementary Section A: the `recent` last positions plus
+    `random` distinct positions drawn uniformly from the rest, ascending."""
+    recent = min(recent, n)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    rest = n - recent
+    rnd = rng.choice(rest, size=min(random, rest), replace=False) if rest > 0 else np.zeros(0, np.int64)
+    return np.sort(np.concatenate([rnd, np.arange(rest, n)])).astype(np.int32)
+
+
 def make_workload(cfg: int, layer: int = 0, gamma: float = GAMMA_DEFAULT,
                   seed: Optional[int] = None, batch: Optional[int] = None) -> Workload:
     """One layer of benchmark shape ``cfg`` (1..5).  ``batch`` overrides B
