@@ -205,6 +205,7 @@ def main():
                     help="probe rows: the last 64 positions (benchmark configs) or the paper's 64 recent + 64 random")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 3 plain device copies of 256 MiB (a kernel of known HBM traffic, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -276,6 +277,43 @@ def main():
     z.zipvl_timing_enable(False)
     ms_per_step = 1e3 * (t1 - t0) / args.steps
 
+    # The same step replayed from a HIP graph (no host launch cost, shorter gaps between the dependent
+    # kernels): reported beside the eager number; every checked replay must reproduce the eager output.
+    graph_ms = None
+    if not args.no_graph:
+        O_ref, idx_ref, k_ref = O.clone(), idx.clone(), k.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        ok = True
+        for _ in range(3):
+            O.fill_(1.0); k.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            ok = ok and torch.equal(O, O_ref) and torch.equal(k, k_ref) and torch.equal(idx, idx_ref)
+            step()                                           # eager work between the replays
+            torch.cuda.synchronize()
+        if ok:
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                g.replay()
+            torch.cuda.synchronize()
+            graph_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        else:
+            graph_ms = None
+    eager_ms = ms_per_step
+    launch_mode = "eager (one C-ABI call per stage, HIP events around every kernel)"
+    if graph_ms is not None:
+        ms_per_step = graph_ms                               # same kernels, same step, replayed from the graph
+        launch_mode = "hipgraph replay of the four C-ABI calls (outputs verified against the eager step)"
+
     k_h = k.cpu().numpy().astype(np.int64)
     G = Hq // Hkv
     dense_flops = 2.0 * B * Hq * d * n * (n + 1)
@@ -332,6 +370,7 @@ def main():
         "k_per_unit": [int(x) for x in k_h[:16]],
         "kernels": kern,
         "hbm_GBps_algorithmic": hbm,
+        "launch": launch_mode, "eager_ms_per_step_with_kernel_events": eager_ms, "hipgraph_ms_per_step": graph_ms,
         "dense_same_kernel_ms": dense_ms,
         "sparse_speedup_vs_dense": (dense_ms / ms_per_step) if dense_ms else None,
         "roofline": roofline,
