@@ -207,17 +207,24 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
     const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ VTp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
-    T* __restrict__ O, int n, int npad, int ntq, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped)
+    T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped)
 {
     using C = AttnCfg<T, D>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    // Workgroup -> (KV head, query tile, head of the group), in that order of significance: the chip
-    // works through one KV head at a time, so every XCD's L2 (workgroups are dealt round-robin to the
-    // 8 XCDs) only has to hold that unit's K / V^T; inside a unit heavy (late) query tiles come first,
-    // and the light tail of one unit overlaps the heavy start of the next.
-    const int G = Hq / Hkv;
-    const int u = blockIdx.x / (ntq * G), rem = blockIdx.x - u * (ntq * G);
-    const int tile_rev = rem / G, hg = rem - tile_rev * G;
+    // Workgroup -> (unit group, query tile, unit in group, head of the KV group), in that order of
+    // significance; heavy (late) query tiles first inside a group.  A group holds just enough KV heads
+    // to fill the chip a few times over (one for long GQA sequences, many for short MHA ones): the
+    // chip then works through few KV heads at a time, so every XCD's L2 (workgroups are dealt
+    // round-robin to the 8 XCDs) holds little more than the K / V^T it is using, while the light tail
+    // of one group overlaps the heavy start of the next.
+    const int G = Hq / Hkv, NU = BH / G;
+    const int full = ug * ntq * G;                           // workgroups of a full group
+    const int ngroups = (NU + ug - 1) / ug;
+    const int grp = min((int)(blockIdx.x / full), ngroups - 1);
+    const int r = blockIdx.x - grp * full;
+    const int nu_g = min(ug, NU - grp * ug);
+    const int tile_rev = r / (nu_g * G), rr = r - tile_rev * (nu_g * G);
+    const int u = grp * ug + rr / G, hg = rr % G;
     const int b = u / Hkv, g = u - b * Hkv, head = g * G + hg, bh = b * Hq + head;
     const int i0 = (ntq - 1 - tile_rev) * kBM;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
@@ -405,11 +412,14 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
         const int BH = d.B * d.Hq;
         const int ntq = (d.n + kBM - 1) / kBM;
         const int64_t blocks = (int64_t)ntq * BH;
+        const int G = d.Hq / d.Hkv;
+        int ug = 1024 / (ntq * G);                          // KV heads per scheduling group (see the kernel)
+        ug = ug < 1 ? 1 : ug;
         if (blocks > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
         hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((unsigned)blocks), dim3(256),
             C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             skip_k ? (const T*)K : (const T*)Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
-            skip_k ? d.k_strides[1] : (int64_t)npad * D, (const T*)VTp, idx, k, (T*)O, d.n, npad, ntq, BH, d.Hq, d.Hkv,
+            skip_k ? d.k_strides[1] : (int64_t)npad * D, (const T*)VTp, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
             scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0);
     }
     return check_launch("flash_kept");

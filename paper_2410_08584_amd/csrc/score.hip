@@ -93,16 +93,21 @@ __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
     constexpr int NPRE = C::GC * kProbes * C::CPR / kScoreThreads;
     static_assert(NPRE * kScoreThreads == C::GC * kProbes * C::CPR, "chunk must divide evenly over the threads");
     uintx4 pre[NPRE];
-    auto fetch_chunk = [&](int h0) {
-        const int total = min(C::GC, G - h0) * kProbes * C::CPR;
+    // where this thread's NPRE chunks sit inside a chunk of heads: fixed for the whole kernel
+    int pre_head[NPRE];
+    int64_t pre_off[NPRE];
 #pragma unroll
-        for (int q = 0; q < NPRE; ++q) {
-            const int t = min(tid + q * kScoreThreads, total - 1);
-            const int row = t / C::CPR, cc = t - row * C::CPR;
-            const int hh = row / kProbes, pc = row - hh * kProbes;
-            const T* src = Q + b * qs0 + (g * G + h0 + hh) * qs1 + (int64_t)sp[min(pc, m - 1)] * qs2;
-            pre[q] = load16(src + cc * Elem<T>::kPerFrag);
-        }
+    for (int q = 0; q < NPRE; ++q) {
+        const int t = tid + q * kScoreThreads;
+        const int row = t / C::CPR, cc = t - row * C::CPR;
+        pre_head[q] = row / kProbes;
+        pre_off[q] = (int64_t)sp[min(row - pre_head[q] * kProbes, m - 1)] * qs2 + cc * Elem<T>::kPerFrag;
+    }
+    auto fetch_chunk = [&](int h0) {
+        const T* base = Q + b * qs0 + (int64_t)(g * G + h0) * qs1;
+        const int last = min(C::GC, G - h0) - 1;               // heads beyond the chunk re-read its last head
+#pragma unroll
+        for (int q = 0; q < NPRE; ++q) pre[q] = load16(base + min(pre_head[q], last) * qs1 + pre_off[q]);
     };
     fetch_chunk(0);
     for (int h0 = 0; h0 < G; h0 += C::GC) {
