@@ -25,12 +25,18 @@
 
 namespace zipvl {
 
-constexpr int kBM = 128;     // queries per workgroup
 constexpr int kBN = 64;      // keys per tile
+constexpr int kFlashWavesBf16 = 4;   // 8 (one workgroup per CU) halves the L2 -> LDS traffic but measured no faster
+constexpr int kSchedAhead = 3;       // LDS operand reads in flight ahead of the consuming MFMA
+constexpr int kSchedValu = 4;        // vector instructions placed between two MFMAs
 
-template <typename T, int D>
+// NW = waves per workgroup; a wave owns 32 queries, so a workgroup covers 32 NW kept queries and its
+// K / V^T tiles are fetched from L2 once per 32 NW queries.
+template <typename T, int D, int NW = 4>
 struct AttnCfg {
     static constexpr int E = Elem<T>::kBytes;
+    static constexpr int BM = 32 * NW;                       // queries per workgroup
+    static constexpr int NT = 64 * NW;                       // threads per workgroup
     static constexpr int CH = D / Elem<T>::kPerChunk;       // Q/K fragments per row per lane
     static constexpr int ODB = D / 32;                       // 32-row blocks of O^T
     // LDS tiles are unpadded; the 16-byte chunks of a row are XOR-swizzled with (row & 7) instead, so
@@ -38,10 +44,10 @@ struct AttnCfg {
     static constexpr int KRB = D * E;                        // bytes per K row
     static constexpr int VRB = kBN * E;                      // bytes per V^T row
     static constexpr int TILE_BYTES = kBN * D * E;           // one K tile = one V^T tile
-    static constexpr int NLD = TILE_BYTES / 1024 / 4;        // 1-KiB direct-to-LDS loads per wave per tile
+    static constexpr int NLD = TILE_BYTES / 1024 / NW;       // 1-KiB direct-to-LDS loads per wave per tile
     static constexpr int LDS_BYTES = 4 * TILE_BYTES;         // two K and two V^T buffers
     static constexpr int NVF = (E == 2 ? 2 : 4) * ODB;       // V^T operand fragments per 32 keys per lane
-    static constexpr int MIN_WAVES = (E == 2) ? 2 : 1;       // bf16: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs)
+    static constexpr int MIN_WGS = (E == 2) ? 8 / NW : 1;    // bf16: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs)
 };
 
 // ------------------------------------------------------------------ pack
@@ -102,48 +108,58 @@ __device__ __forceinline__ int swz_chunk(int c, int sw) { return (c ^ sw) << 4; 
 // One tile (TILE_BYTES contiguous in global memory) -> one LDS buffer, without passing through
 // registers: every wave issues NLD loads of 1 KiB, lane L of a load writes LDS bytes [16 L, 16 L + 16)
 // of that KiB, and picks the global chunk that belongs there under the row swizzle.
-template <typename T, int D>
-__device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w, const int (&off)[AttnCfg<T, D>::NLD]) {
+// One 1-KiB direct-to-LDS load of the wave: lane L's 16 bytes at gsrc land at LDS byte lds_base + 16 L.
+// global_load_lds_dwordx4 takes the LDS base from M0.  The instruction is written out rather than
+// taken from the builtin because the compiler, while such a load is pending, turns every LDS-read
+// wait into a wait for ALL outstanding LDS reads, which stalls the matrix pipeline on each operand
+// fetch; completion is awaited explicitly (vmcnt) at the end of every pipeline step instead.
+__device__ __forceinline__ void load_kib_to_lds(const char* gsrc, unsigned lds_base) {
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(m0v), "v"(gsrc) : "memory", "m0");
+}
+
+__device__ __forceinline__ unsigned lds_address(const char* p) {
+    return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+template <int NW, int NLD>
+__device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w, const int (&off)[NLD]) {
+    const unsigned lbase = lds_address(lbuf);
 #pragma unroll
-    for (int q = 0; q < AttnCfg<T, D>::NLD; ++q)
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(gtile + off[q]),
-            (__attribute__((address_space(3))) void*)(lbuf + (q * 4 + w) * 1024), 16, 0, 0);
+    for (int q = 0; q < NLD; ++q) load_kib_to_lds(gtile + off[q], lbase + (q * NW + w) * 1024);
 }
 
 // per-lane source offsets for tile_to_lds (rows of RB bytes)
-template <int RB, int NLD>
+template <int RB, int NW, int NLD>
 __device__ __forceinline__ void lds_fill_offsets(int w, int lane, int (&off)[NLD]) {
 #pragma unroll
     for (int q = 0; q < NLD; ++q) {
-        const int o = (q * 4 + w) * 1024 + lane * 16;
+        const int o = (q * NW + w) * 1024 + lane * 16;
         const int r = o / RB, p = (o % RB) >> 4;
         off[q] = r * RB + ((p ^ (r & 7)) << 4);
     }
 }
 
-// S^T = K Q^T for one 64-key tile held in LDS buffer kb: acc[blk][r] = key 32*blk + acc_row(r, h), this lane's query
-template <typename T, int D>
-__device__ __forceinline__ void qk_tile(const char* kb, int i, int h, int sw, const uintx4 (&qf)[AttnCfg<T, D>::CH],
-                                        floatx16 (&acc)[2]) {
-    using C = AttnCfg<T, D>;
+// S^T = K Q^T for 32 keys (block blk of the 64-key tile in LDS buffer kb): acc[r] = key 32*blk + acc_row(r, h), this lane's query
+template <typename T, int D, int NW>
+__device__ __forceinline__ void qk_block(const char* kb, int blk, int i, int h, int sw,
+                                         const uintx4 (&qf)[AttnCfg<T, D, NW>::CH], floatx16& acc) {
+    using C = AttnCfg<T, D, NW>;
+    floatx16 a = {0};
 #pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-        floatx16 a = {0};
-#pragma unroll
-        for (int cc = 0; cc < C::CH; ++cc) {
-            const uintx4 kf = *reinterpret_cast<const uintx4*>(kb + (blk * 32 + i) * C::KRB + swz_chunk(2 * cc + h, sw));
-            a = mma_frag<T>(kf, qf[cc], a);
-        }
-        acc[blk] = a;
+    for (int cc = 0; cc < C::CH; ++cc) {
+        const uintx4 kf = *reinterpret_cast<const uintx4*>(kb + (blk * 32 + i) * C::KRB + swz_chunk(2 * cc + h, sw));
+        a = mma_frag<T>(kf, qf[cc], a);
     }
+    acc = a;
 }
 
 // O^T += V^T P^T for the 32 keys of half HALF: p[16] holds the probabilities of S^T block HALF.
-template <typename T, int D> struct PV;
+template <typename T, int D, int NW> struct PV;
 
-template <int D> struct PV<__bf16, D> {
-    using C = AttnCfg<__bf16, D>;
+template <int D, int NW> struct PV<__bf16, D, NW> {
+    using C = AttnCfg<__bf16, D, NW>;
     template <int HALF>
     __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const floatx16& p, floatx16 (&o)[C::ODB]) {
 #pragma unroll
@@ -165,8 +181,8 @@ template <int D> struct PV<__bf16, D> {
     }
 };
 
-template <int D> struct PV<float, D> {
-    using C = AttnCfg<float, D>;
+template <int D, int NW> struct PV<float, D, NW> {
+    using C = AttnCfg<float, D, NW>;
     template <int HALF>
     __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const floatx16& p, floatx16 (&o)[C::ODB]) {
 #pragma unroll
@@ -183,6 +199,24 @@ template <int D> struct PV<float, D> {
         }
     }
 };
+
+// Instruction order of the steady-state step (one basic block: S^T of the next tile, exponentials and
+// P.V of the current one): LDS operand reads run a few fragments ahead of the matrix instruction that
+// consumes them and the vector work is spread evenly between the matrix instructions, so that a wave
+// neither waits on LDS latency in front of every MFMA nor bunches its vector work.
+template <typename T, int D>
+__device__ __forceinline__ void flash_schedule() {
+    if constexpr (Elem<T>::kBytes == 2 && D == 128) {
+#pragma unroll
+        for (int q = 0; q < kSchedAhead; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+#pragma unroll
+        for (int q = 0; q < 32; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                        // LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, kSchedValu, 0);         // vector ALU
+        }
+    }
+}
 
 // rows [lo, hi) of head bh of O := 0, spread over `nthreads` threads (16-byte stores)
 template <typename T, int D>
@@ -202,14 +236,15 @@ template <> __device__ __forceinline__ void store_out4<__bf16>(__bf16* dst, floa
     *reinterpret_cast<uintx2*>(dst) = uintx2{pack_bf16x2(a, b), pack_bf16x2(c, d)};
 }
 
-template <typename T, int D>
-__global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_kernel(
+template <typename T, int D, int NW>
+__global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW>::MIN_WGS)) void flash_kept_kernel(
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
     const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ VTp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
     T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped)
 {
-    using C = AttnCfg<T, D>;
+    using C = AttnCfg<T, D, NW>;
+    constexpr int kBM = C::BM, kNT = C::NT;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     // Workgroup -> (unit group, query tile, unit in group, head of the KV group), in that order of
     // significance; heavy (late) query tiles first inside a group.  A group holds just enough KV heads
@@ -231,7 +266,7 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
     int kk = kcnt ? kcnt[u] : n;
     kk = max(0, min(kk, n));
     if (i0 >= kk) {
-        if (zero_dropped && i0 == 0) zero_rows<T, D>(O, bh, n, 0, n, tid, 256);   // nothing kept at all
+        if (zero_dropped && i0 == 0) zero_rows<T, D>(O, bh, n, 0, n, tid, kNT);   // nothing kept at all
         return;
     }
     if (zero_dropped) {
@@ -243,7 +278,7 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
             tpos[tid] = r < 0 ? -1 : (r < kk ? idx[(int64_t)u * n + r] : n);
         }
         __syncthreads();
-        if (i0 + kBM == kk) zero_rows<T, D>(O, bh, n, tpos[kBM] + 1, n, tid, 256);   // tail after a full last tile
+        if (i0 + kBM == kk) zero_rows<T, D>(O, bh, n, tpos[kBM] + 1, n, tid, kNT);   // tail after a full last tile
 #pragma unroll
         for (int half = 0; half < kBM / 64; ++half) {
             const int gi = half * 64 + lane;
@@ -251,7 +286,7 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
             while (open) {                                   // wave-uniform walk over the non-empty gaps
                 const int gsel = half * 64 + __builtin_ctzll(open);
                 open &= open - 1;
-                zero_rows<T, D>(O, bh, n, tpos[gsel] + 1, tpos[gsel + 1], tid, 256);
+                zero_rows<T, D>(O, bh, n, tpos[gsel] + 1, tpos[gsel + 1], tid, kNT);
             }
         }
         __syncthreads();                                     // tpos is overwritten by the first K tile
@@ -280,23 +315,25 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
     char* const Vb0 = smem + 2 * C::TILE_BYTES;
     const int sw = i & 7;
     int koff[C::NLD], voff[C::NLD];
-    lds_fill_offsets<C::KRB, C::NLD>(w, lane, koff);
-    lds_fill_offsets<C::VRB, C::NLD>(w, lane, voff);
+    lds_fill_offsets<C::KRB, NW, C::NLD>(w, lane, koff);
+    lds_fill_offsets<C::VRB, NW, C::NLD>(w, lane, voff);
 
     // Software pipeline over key tiles.  While tile t is in its softmax (vector ALU) and P.V (matrix)
     // stages, the S^T product of tile t+1 already runs on the matrix cores and the loads of K tile t+2
     // and V^T tile t+1 are in flight straight into LDS.  One barrier per tile.
-    tile_to_lds<T, D>(kg, Kb0, w, koff);
-    tile_to_lds<T, D>(vg, Vb0, w, voff);
-    if (ntiles > 1) tile_to_lds<T, D>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
+    tile_to_lds<NW, C::NLD>(kg, Kb0, w, koff);
+    tile_to_lds<NW, C::NLD>(vg, Vb0, w, voff);
+    if (ntiles > 1) tile_to_lds<NW, C::NLD>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     floatx16 sa[2], sb[2];
-    qk_tile<T, D>(Kb0, i, h, sw, qf, sa);                   // tile 0 is visible to every row
+    qk_block<T, D, NW>(Kb0, 0, i, h, sw, qf, sa[0]);        // tile 0 is visible to every row
+    qk_block<T, D, NW>(Kb0, 1, i, h, sw, qf, sa[1]);
 
     auto step = [&](int t, floatx16 (&sc)[2], floatx16 (&sn)[2]) {
-        if (t + 2 < ntiles) tile_to_lds<T, D>(kg + (int64_t)(t + 2) * C::TILE_BYTES, Kb0 + (t & 1) * C::TILE_BYTES, w, koff);
-        if (t + 1 < ntiles) tile_to_lds<T, D>(vg + (int64_t)(t + 1) * C::TILE_BYTES, Vb0 + ((t + 1) & 1) * C::TILE_BYTES, w, voff);
+        // this step's loads: K tile t+2 into the buffer tile t has left, V^T tile t+1 into the one tile t-1 has left
+        if (t + 2 < ntiles) tile_to_lds<NW, C::NLD>(kg + (int64_t)(t + 2) * C::TILE_BYTES, Kb0 + (t & 1) * C::TILE_BYTES, w, koff);
+        if (t + 1 < ntiles) tile_to_lds<NW, C::NLD>(vg + (int64_t)(t + 1) * C::TILE_BYTES, Vb0 + ((t + 1) & 1) * C::TILE_BYTES, w, voff);
         if (t < my_tiles) {
             const int t0 = t * kBN;
             const char* kb = Kb0 + ((t + 1) & 1) * C::TILE_BYTES;
@@ -329,20 +366,22 @@ __global__ __launch_bounds__(256, (AttnCfg<T, D>::MIN_WAVES)) void flash_kept_ke
             float sum = 0.f;
             if (t + 1 < my_tiles) {
                 // matrix stream: S^T of tile t+1, then P.V of tile t; vector stream: exponentials of tile t
-                qk_tile<T, D>(kb, i, h, sw, qf, sn);
+                qk_block<T, D, NW>(kb, 0, i, h, sw, qf, sn[0]);
+                qk_block<T, D, NW>(kb, 1, i, h, sw, qf, sn[1]);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) { sc[0][r] = fast_exp2(fmaf(sc[0][r], c, -mc)); sum += sc[0][r]; }
-                PV<T, D>::template run<0>(vb, i, h, sw, sc[0], o);
+                PV<T, D, NW>::template run<0>(vb, i, h, sw, sc[0], o);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) { sc[1][r] = fast_exp2(fmaf(sc[1][r], c, -mc)); sum += sc[1][r]; }
-                PV<T, D>::template run<1>(vb, i, h, sw, sc[1], o);
+                PV<T, D, NW>::template run<1>(vb, i, h, sw, sc[1], o);
+                flash_schedule<T, D>();
             } else {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) { sc[0][r] = fast_exp2(fmaf(sc[0][r], c, -mc)); sum += sc[0][r]; }
-                PV<T, D>::template run<0>(vb, i, h, sw, sc[0], o);
+                PV<T, D, NW>::template run<0>(vb, i, h, sw, sc[0], o);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) { sc[1][r] = fast_exp2(fmaf(sc[1][r], c, -mc)); sum += sc[1][r]; }
-                PV<T, D>::template run<1>(vb, i, h, sw, sc[1], o);
+                PV<T, D, NW>::template run<1>(vb, i, h, sw, sc[1], o);
             }
             l_run += sum;
         }
@@ -375,12 +414,41 @@ size_t prefill_workspace_bytes(const zipvl_dims& d) {
     return 2 * (size_t)d.B * d.Hkv * npad * d.d * e;
 }
 
+template <typename T, int D, int NW>
+static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const int32_t* idx, const int32_t* k,
+                        float scale, int out_compact, int skip_k, const T* Kp, const T* VTp, int npad, void* O, hipStream_t st)
+{
+    using C = AttnCfg<T, D, NW>;
+    static bool attr_done = false;       // raising the dynamic-LDS cap is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kept_kernel<T, D, NW>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
+            return set_error(ZIPVL_EHIP, "sparse_prefill: cannot reserve %d bytes of LDS", C::LDS_BYTES);
+        attr_done = true;
+    }
+    {
+        KernelTimer tm(ZIPVL_K_FLASH_KEPT, st);
+        const int BH = d.B * d.Hq;
+        const int ntq = (d.n + C::BM - 1) / C::BM;
+        const int64_t blocks = (int64_t)ntq * BH;
+        const int G = d.Hq / d.Hkv;
+        int ug = (4096 / NW) / (ntq * G);                   // KV heads per scheduling group (see the kernel)
+        ug = ug < 1 ? 1 : ug;
+        if (blocks > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
+        hipLaunchKernelGGL((flash_kept_kernel<T, D, NW>), dim3((unsigned)blocks), dim3(C::NT),
+            C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
+            skip_k ? (const T*)K : Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
+            skip_k ? d.k_strides[1] : (int64_t)npad * D, VTp, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
+            scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0);
+    }
+    return check_launch("flash_kept");
+}
+
 template <typename T, int D>
 static int launch_prefill_t(const void* Q, const void* K, const void* V, const zipvl_dims& d,
                             const int32_t* idx, const int32_t* k, float scale, int flags,
                             void* O, void* ws, hipStream_t st)
 {
-    using C = AttnCfg<T, D>;
     const int npad = (d.n + kBN - 1) / kBN * kBN;
     const int units = d.B * d.Hkv;
     T* Kp = (T*)ws;
@@ -400,29 +468,12 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     int rc = check_launch("pack_kv");
     if (rc) return rc;
 
-    static bool attr_done = false;       // raising the dynamic-LDS cap is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kept_kernel<T, D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
-            return set_error(ZIPVL_EHIP, "sparse_prefill: cannot reserve %d bytes of LDS", C::LDS_BYTES);
-        attr_done = true;
-    }
-    {
-        KernelTimer tm(ZIPVL_K_FLASH_KEPT, st);
-        const int BH = d.B * d.Hq;
-        const int ntq = (d.n + kBM - 1) / kBM;
-        const int64_t blocks = (int64_t)ntq * BH;
-        const int G = d.Hq / d.Hkv;
-        int ug = 1024 / (ntq * G);                          // KV heads per scheduling group (see the kernel)
-        ug = ug < 1 ? 1 : ug;
-        if (blocks > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
-        hipLaunchKernelGGL((flash_kept_kernel<T, D>), dim3((unsigned)blocks), dim3(256),
-            C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-            skip_k ? (const T*)K : (const T*)Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
-            skip_k ? d.k_strides[1] : (int64_t)npad * D, (const T*)VTp, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
-            scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0);
-    }
-    return check_launch("flash_kept");
+    // bf16: 8 waves share every tile (half the L2 -> LDS traffic per query); fp32 keeps 4 waves
+    // (its tiles are twice as large and it runs one wave per SIMD).
+    if constexpr (Elem<T>::kBytes == 2)
+        return launch_flash<T, D, kFlashWavesBf16>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
+    else
+        return launch_flash<T, D, 4>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
 }
 
 int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims& d,
