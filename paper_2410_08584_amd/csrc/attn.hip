@@ -26,16 +26,25 @@
 namespace zipvl {
 
 constexpr int kBN = 64;      // keys per tile
-constexpr int kFlashWavesBf16 = 4;   // 8 (one workgroup per CU) halves the L2 -> LDS traffic but measured no faster
+#ifndef ZIPVL_FLASH_WAVES_BF16
+#define ZIPVL_FLASH_WAVES_BF16 4
+#endif
+#ifndef ZIPVL_FLASH_QB_BF16
+#define ZIPVL_FLASH_QB_BF16 1
+#endif
+constexpr int kFlashWavesBf16 = ZIPVL_FLASH_WAVES_BF16;
+constexpr int kFlashBlocksBf16 = ZIPVL_FLASH_QB_BF16;
+constexpr float kLazyLog2 = 8.f;     // slack of the running softmax offset below the running maximum (log2 domain)
 constexpr int kSchedAhead = 3;       // LDS operand reads in flight ahead of the consuming MFMA
 constexpr int kSchedValu = 4;        // vector instructions placed between two MFMAs
 
-// NW = waves per workgroup; a wave owns 32 queries, so a workgroup covers 32 NW kept queries and its
-// K / V^T tiles are fetched from L2 once per 32 NW queries.
-template <typename T, int D, int NW = 4>
+// NW = waves per workgroup, QB = 32-query blocks per wave: a workgroup covers 32 QB NW kept queries, its
+// K / V^T tiles are fetched from L2 once per that many queries, and every LDS operand fragment a wave
+// reads feeds QB matrix instructions.
+template <typename T, int D, int NW = 4, int QB = 1>
 struct AttnCfg {
     static constexpr int E = Elem<T>::kBytes;
-    static constexpr int BM = 32 * NW;                       // queries per workgroup
+    static constexpr int BM = 32 * QB * NW;                  // queries per workgroup
     static constexpr int NT = 64 * NW;                       // threads per workgroup
     static constexpr int CH = D / Elem<T>::kPerChunk;       // Q/K fragments per row per lane
     static constexpr int ODB = D / 32;                       // 32-row blocks of O^T
@@ -46,8 +55,9 @@ struct AttnCfg {
     static constexpr int TILE_BYTES = kBN * D * E;           // one K tile = one V^T tile
     static constexpr int NLD = TILE_BYTES / 1024 / NW;       // 1-KiB direct-to-LDS loads per wave per tile
     static constexpr int LDS_BYTES = 4 * TILE_BYTES;         // two K and two V^T buffers
-    static constexpr int NVF = (E == 2 ? 2 : 4) * ODB;       // V^T operand fragments per 32 keys per lane
-    static constexpr int MIN_WGS = (E == 2) ? 8 / NW : 1;    // bf16: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs)
+    // bf16, QB = 1: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs); otherwise one
+    // wave per SIMD with the whole 512-entry register file
+    static constexpr int MIN_WGS = (E == 2 && QB == 1) ? 8 / NW : 1;
 };
 
 // ------------------------------------------------------------------ pack
@@ -108,15 +118,27 @@ __device__ __forceinline__ int swz_chunk(int c, int sw) { return (c ^ sw) << 4; 
 // One tile (TILE_BYTES contiguous in global memory) -> one LDS buffer, without passing through
 // registers: every wave issues NLD loads of 1 KiB, lane L of a load writes LDS bytes [16 L, 16 L + 16)
 // of that KiB, and picks the global chunk that belongs there under the row swizzle.
-// One 1-KiB direct-to-LDS load of the wave: lane L's 16 bytes at gsrc land at LDS byte lds_base + 16 L.
+// One 1-KiB direct-to-LDS load of the wave: lane L's 16 bytes at gbase + goff land at LDS byte
+// lds_base + 16 L (gbase and lds_base wave-uniform, goff a per-lane byte offset below 4 GiB).
 // global_load_lds_dwordx4 takes the LDS base from M0.  The instruction is written out rather than
 // taken from the builtin because the compiler, while such a load is pending, turns every LDS-read
 // wait into a wait for ALL outstanding LDS reads, which stalls the matrix pipeline on each operand
 // fetch; completion is awaited explicitly (vmcnt) at the end of every pipeline step instead.
-__device__ __forceinline__ void load_kib_to_lds(const char* gsrc, unsigned lds_base) {
+__device__ __forceinline__ void load_kib_to_lds(const char* gbase, int goff, unsigned lds_base) {
     const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(m0v), "v"(gsrc) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(m0v), "v"(goff), "s"(gbase) : "memory", "m0");
+}
+
+// The same load, placed by data flow instead of by program order: it is tied to a register (`pin`, passed
+// through unchanged) so that it issues after the instruction that produced `pin` and before the one that
+// consumes it, without ordering the surrounding LDS reads the way a statement with side effects would.
+// Used to spread a step's loads between its matrix instructions; the buffers written are not read before
+// the barrier that ends the step, and that barrier is preceded by a wait for all of the wave's loads.
+__device__ __forceinline__ void load_kib_to_lds_pinned(const char* gbase, int goff, unsigned lds_base, unsigned& pin) {
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);
+    asm("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
+        : "+v"(pin) : "s"(m0v), "v"(goff), "s"(gbase) : "m0");
 }
 
 __device__ __forceinline__ unsigned lds_address(const char* p) {
@@ -127,7 +149,7 @@ template <int NW, int NLD>
 __device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w, const int (&off)[NLD]) {
     const unsigned lbase = lds_address(lbuf);
 #pragma unroll
-    for (int q = 0; q < NLD; ++q) load_kib_to_lds(gtile + off[q], lbase + (q * NW + w) * 1024);
+    for (int q = 0; q < NLD; ++q) load_kib_to_lds(gtile, off[q], lbase + (q * NW + w) * 1024);
 }
 
 // per-lane source offsets for tile_to_lds (rows of RB bytes)
@@ -141,50 +163,54 @@ __device__ __forceinline__ void lds_fill_offsets(int w, int lane, int (&off)[NLD
     }
 }
 
-// S^T = K Q^T for 32 keys (block blk of the 64-key tile in LDS buffer kb): acc[r] = key 32*blk + acc_row(r, h), this lane's query
-template <typename T, int D, int NW>
+// S^T = K Q^T for 32 keys (block blk of the 64-key tile in LDS buffer kb) and the wave's QB query blocks:
+// acc[qb][blk][r] = key 32*blk + acc_row(r, h), this lane's query of block qb.  A K fragment is read once for all QB.
+template <typename T, int D, int NW, int QB>
 __device__ __forceinline__ void qk_block(const char* kb, int blk, int i, int h, int sw,
-                                         const uintx4 (&qf)[AttnCfg<T, D, NW>::CH], floatx16& acc) {
-    using C = AttnCfg<T, D, NW>;
-    floatx16 a = {0};
+                                         const uintx4 (&qf)[QB][AttnCfg<T, D, NW, QB>::CH], floatx16 (&acc)[QB][2]) {
+    using C = AttnCfg<T, D, NW, QB>;
+    floatx16 a[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) a[qb] = floatx16{0};
 #pragma unroll
     for (int cc = 0; cc < C::CH; ++cc) {
         const uintx4 kf = *reinterpret_cast<const uintx4*>(kb + (blk * 32 + i) * C::KRB + swz_chunk(2 * cc + h, sw));
-        a = mma_frag<T>(kf, qf[cc], a);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) a[qb] = mma_frag<T>(kf, qf[qb][cc], a[qb]);
     }
-    acc = a;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) acc[qb][blk] = a[qb];
 }
 
-// O^T += V^T P^T for the 32 keys of half HALF: p[16] holds the probabilities of S^T block HALF.
-template <typename T, int D, int NW> struct PV;
+// O^T += V^T P^T for the 32 keys of half HALF: p[qb][HALF] holds the probabilities of S^T block HALF of query block qb.
+template <typename T, int D, int NW, int QB> struct PV;
 
-template <int D, int NW> struct PV<__bf16, D, NW> {
-    using C = AttnCfg<__bf16, D, NW>;
+template <int D, int NW, int QB> struct PV<__bf16, D, NW, QB> {
+    using C = AttnCfg<__bf16, D, NW, QB>;
+    // p[qb][blk][s2]: the probabilities of S^T block blk as P^T operand fragments.  Contraction slot t of
+    // this lane <-> key 16*s2 + 8*(t/4) + 4*h + t%4 of the block = accumulator register 8*s2 + t; V^T rows
+    // are stored in slot order, so the matching V^T operand is one 16-byte chunk.
+    using Probs = uintx4[QB][2][2];
     template <int HALF>
-    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const floatx16& p, floatx16 (&o)[C::ODB]) {
+    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const Probs& p, floatx16 (&o)[QB][C::ODB]) {
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-            // contraction slot t of this lane <-> key 16*s2 + 8*(t/4) + 4*h + t%4 of the half = register 8*s2 + t;
-            // V^T rows are stored in slot order, so the matching operand is one 16-byte chunk
-            uintx4 bfrag;
-            bfrag[0] = pack_bf16x2(p[8 * s2 + 0], p[8 * s2 + 1]);
-            bfrag[1] = pack_bf16x2(p[8 * s2 + 2], p[8 * s2 + 3]);
-            bfrag[2] = pack_bf16x2(p[8 * s2 + 4], p[8 * s2 + 5]);
-            bfrag[3] = pack_bf16x2(p[8 * s2 + 6], p[8 * s2 + 7]);
             const int chunk = swz_chunk(2 * (2 * HALF + s2) + h, sw);
 #pragma unroll
             for (int db = 0; db < C::ODB; ++db) {
                 const uintx4 vf = *reinterpret_cast<const uintx4*>(vb + (db * 32 + i) * C::VRB + chunk);
-                o[db] = mma_frag<__bf16>(vf, bfrag, o[db]);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) o[qb][db] = mma_frag<__bf16>(vf, p[qb][HALF][s2], o[qb][db]);
             }
         }
     }
 };
 
-template <int D, int NW> struct PV<float, D, NW> {
-    using C = AttnCfg<float, D, NW>;
+template <int D, int NW, int QB> struct PV<float, D, NW, QB> {
+    using C = AttnCfg<float, D, NW, QB>;
+    using Probs = floatx16[QB][2];                           // p[qb][blk][r]: as the S^T accumulators
     template <int HALF>
-    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const floatx16& p, floatx16 (&o)[C::ODB]) {
+    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const Probs& p, floatx16 (&o)[QB][C::ODB]) {
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             // step (a, t): this lane contributes key 32*HALF + 8*a + 4*h + t
@@ -194,26 +220,28 @@ template <int D, int NW> struct PV<float, D, NW> {
                 const floatx4 v = *reinterpret_cast<const floatx4*>(vb + (db * 32 + i) * C::VRB + chunk);
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x2f32(v[t], p[4 * a + t], o[db], 0, 0, 0);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+                        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x2f32(v[t], p[qb][HALF][4 * a + t], o[qb][db], 0, 0, 0);
             }
         }
     }
 };
 
 // Instruction order of the steady-state step (one basic block: S^T of the next tile, exponentials and
-// P.V of the current one): LDS operand reads run a few fragments ahead of the matrix instruction that
-// consumes them and the vector work is spread evenly between the matrix instructions, so that a wave
+// P.V of the current one): LDS operand reads run a few fragments ahead of the matrix instructions that
+// consume them and the vector work is spread evenly between the matrix instructions, so that a wave
 // neither waits on LDS latency in front of every MFMA nor bunches its vector work.
-template <typename T, int D>
+template <typename T, int D, int QB>
 __device__ __forceinline__ void flash_schedule() {
     if constexpr (Elem<T>::kBytes == 2 && D == 128) {
 #pragma unroll
         for (int q = 0; q < kSchedAhead; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
 #pragma unroll
         for (int q = 0; q < 32; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                       // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                        // LDS read
-            __builtin_amdgcn_sched_group_barrier(0x002, kSchedValu, 0);         // vector ALU
+            __builtin_amdgcn_sched_group_barrier(0x002, kSchedValu * QB, 0);          // vector ALU
         }
     }
 }
@@ -228,6 +256,19 @@ __device__ __forceinline__ void zero_rows(T* O, int bh, int n, int lo, int hi, i
     for (int64_t q = tid; q < chunks; q += nthreads) store16(base + q * 16, z);
 }
 
+// The two half-waves (lanes l and l ^ 32) hold the two halves of each query's keys: combine a per-lane
+// value across them with one register swap (no trip through LDS).
+__device__ __forceinline__ float xhalf_max(float v) {
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);   // r[0] = lower halves twice, r[1] = upper halves twice
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float v) {
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <typename T> __device__ __forceinline__ void store_out4(T* dst, float a, float b, float c, float d);
 template <> __device__ __forceinline__ void store_out4<float>(float* dst, float a, float b, float c, float d) {
     *reinterpret_cast<floatx4*>(dst) = floatx4{a, b, c, d};
@@ -236,15 +277,15 @@ template <> __device__ __forceinline__ void store_out4<__bf16>(__bf16* dst, floa
     *reinterpret_cast<uintx2*>(dst) = uintx2{pack_bf16x2(a, b), pack_bf16x2(c, d)};
 }
 
-template <typename T, int D, int NW>
-__global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW>::MIN_WGS)) void flash_kept_kernel(
+template <typename T, int D, int NW, int QB>
+__global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void flash_kept_kernel(
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
     const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ VTp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
     T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped)
 {
-    using C = AttnCfg<T, D, NW>;
-    constexpr int kBM = C::BM, kNT = C::NT;
+    using C = AttnCfg<T, D, NW, QB>;
+    constexpr int kBM = C::BM, kNT = C::NT, kRW = 32 * QB;   // queries per workgroup, threads, queries per wave
     extern __shared__ __attribute__((aligned(16))) char smem[];
     // Workgroup -> (unit group, query tile, unit in group, head of the KV group), in that order of
     // significance; heavy (late) query tiles first inside a group.  A group holds just enough KV heads
@@ -273,9 +314,9 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW>::MIN_WGS)) void flash_k
         // Outputs of dropped tokens are zero rows.  This workgroup clears the dropped positions that
         // lie before each of its kept rows; the tile holding the last kept row also clears the tail.
         int* tpos = reinterpret_cast<int*>(smem);            // [kBM + 1], dead before the first tile is staged
-        if (tid <= kBM) {
-            const int r = i0 - 1 + tid;                      // entry e: position of kept row i0 - 1 + e
-            tpos[tid] = r < 0 ? -1 : (r < kk ? idx[(int64_t)u * n + r] : n);
+        for (int e = tid; e <= kBM; e += kNT) {
+            const int r = i0 - 1 + e;                        // entry e: position of kept row i0 - 1 + e
+            tpos[e] = r < 0 ? -1 : (r < kk ? idx[(int64_t)u * n + r] : n);
         }
         __syncthreads();
         if (i0 + kBM == kk) zero_rows<T, D>(O, bh, n, tpos[kBM] + 1, n, tid, kNT);   // tail after a full last tile
@@ -291,23 +332,30 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW>::MIN_WGS)) void flash_k
         }
         __syncthreads();                                     // tpos is overwritten by the first K tile
     }
-    const int qrow = i0 + 32 * w + i;                        // kept-token coordinate of this lane's query
-    const int qclamp = min(qrow, kk - 1);
-    const int qpos = idx ? idx[(int64_t)u * n + qclamp] : qclamp;
-
-    uintx4 qf[C::CH];
-    {
-        const T* qp = Q + b * qs0 + head * qs1 + (int64_t)qpos * qs2;
+    // kept-token coordinates of this lane's QB queries, their positions, their Q fragments
+    int qrow[QB], qpos[QB];
+    uintx4 qf[QB][C::CH];
 #pragma unroll
-        for (int cc = 0; cc < C::CH; ++cc) qf[cc] = load16(qp + cc * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
+    for (int qb = 0; qb < QB; ++qb) {
+        qrow[qb] = i0 + kRW * w + 32 * qb + i;
+        const int qclamp = min(qrow[qb], kk - 1);
+        qpos[qb] = idx ? idx[(int64_t)u * n + qclamp] : qclamp;
+        const T* qp = Q + b * qs0 + head * qs1 + (int64_t)qpos[qb] * qs2;
+#pragma unroll
+        for (int cc = 0; cc < C::CH; ++cc) qf[qb][cc] = load16(qp + cc * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
     }
-    floatx16 o[C::ODB];
+    floatx16 o[QB][C::ODB];
+    float m_run[QB], l_run[QB];
 #pragma unroll
-    for (int db = 0; db < C::ODB; ++db) o[db] = floatx16{0};
-    float m_run = -INFINITY, l_run = 0.f;
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < C::ODB; ++db) o[qb][db] = floatx16{0};
+    }
 
     const int ntiles = (min(i0 + kBM, kk) + kBN - 1) / kBN;
-    const int wave_first_row = i0 + 32 * w, wave_last_row = wave_first_row + 31;
+    const int wave_first_row = i0 + kRW * w, wave_last_row = wave_first_row + kRW - 1;
     const int my_tiles = min(ntiles, wave_last_row / kBN + 1);   // later tiles lie wholly in this wave's future
     const char* kg = reinterpret_cast<const char*>(Kp + b * kp0 + g * kp1);   // row-major kept K rows of this unit
     const char* vg = reinterpret_cast<const char*>(VTp + (int64_t)u * npad * D);
@@ -326,64 +374,134 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW>::MIN_WGS)) void flash_k
     if (ntiles > 1) tile_to_lds<NW, C::NLD>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    floatx16 sa[2], sb[2];
-    qk_block<T, D, NW>(Kb0, 0, i, h, sw, qf, sa[0]);        // tile 0 is visible to every row
-    qk_block<T, D, NW>(Kb0, 1, i, h, sw, qf, sa[1]);
+    floatx16 sa[QB][2], sb[QB][2];
+    qk_block<T, D, NW, QB>(Kb0, 0, i, h, sw, qf, sa);       // tile 0 is visible to every row
+    qk_block<T, D, NW, QB>(Kb0, 1, i, h, sw, qf, sa);
+    const unsigned klds = lds_address(Kb0) + w * 1024, vlds = lds_address(Vb0) + w * 1024;
 
-    auto step = [&](int t, floatx16 (&sc)[2], floatx16 (&sn)[2]) {
-        // this step's loads: K tile t+2 into the buffer tile t has left, V^T tile t+1 into the one tile t-1 has left
-        if (t + 2 < ntiles) tile_to_lds<NW, C::NLD>(kg + (int64_t)(t + 2) * C::TILE_BYTES, Kb0 + (t & 1) * C::TILE_BYTES, w, koff);
-        if (t + 1 < ntiles) tile_to_lds<NW, C::NLD>(vg + (int64_t)(t + 1) * C::TILE_BYTES, Vb0 + ((t + 1) & 1) * C::TILE_BYTES, w, voff);
+    auto step = [&](int t, floatx16 (&sc)[QB][2], floatx16 (&sn)[QB][2]) {
+        // This step's loads: K tile t+2 into the buffer tile t has left, V^T tile t+1 into the one tile t-1
+        // has left.  In the steady state they are issued one at a time, spread over the step by tying
+        // each to one of the exponentials (a burst of them stalls every wave of the workgroup at the
+        // address unit right after the barrier); elsewhere in one go.  Past the last tile the last
+        // tile is fetched again, unread.
+        const char* kgt = kg + (int64_t)min(t + 2, ntiles - 1) * C::TILE_BYTES;
+        const char* vgt = vg + (int64_t)min(t + 1, ntiles - 1) * C::TILE_BYTES;
+        const unsigned kl = klds + (t & 1) * C::TILE_BYTES, vl = vlds + ((t + 1) & 1) * C::TILE_BYTES;
+        auto fetch_all = [&]() {
+#pragma unroll
+            for (int q = 0; q < C::NLD; ++q) load_kib_to_lds(kgt, koff[q], kl + q * NW * 1024);
+#pragma unroll
+            for (int q = 0; q < C::NLD; ++q) load_kib_to_lds(vgt, voff[q], vl + q * NW * 1024);
+        };
+        // one load after exponential r (of 16) of key block blk: K tile loads ride on block 0, V^T on block 1
+        auto fetch_after_exp = [&](int blk, int r, float& pinned) {
+#pragma unroll
+            for (int q = 0; q < C::NLD; ++q)
+                if (r == ((2 * q + 1) * 16) / (2 * C::NLD)) {
+                    unsigned pin = __float_as_uint(pinned);
+                    if (blk == 0) load_kib_to_lds_pinned(kgt, koff[q], kl + q * NW * 1024, pin);
+                    else load_kib_to_lds_pinned(vgt, voff[q], vl + q * NW * 1024, pin);
+                    pinned = __uint_as_float(pin);
+                }
+        };
         if (t < my_tiles) {
             const int t0 = t * kBN;
             const char* kb = Kb0 + ((t + 1) & 1) * C::TILE_BYTES;
             const char* vb = Vb0 + (t & 1) * C::TILE_BYTES;
             if (t0 + kBN - 1 > wave_first_row) {             // tile touches the diagonal (wave-uniform)
 #pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (t0 + 32 * blk + acc_row(r, h) > qrow[qb]) sc[qb][blk][r] = -INFINITY;
+            }
+            // raw-logit maxima; the softmax scale (c > 0, log2 domain) is folded into the exponent
+            float m_new[QB], mc[QB];
+            const float lazy = kLazyLog2 / c;
+            bool moved = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float mx = -INFINITY;
+#pragma unroll
                 for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (t0 + 32 * blk + acc_row(r, h) > qrow) sc[blk][r] = -INFINITY;
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[qb][blk][r]);
+                mx = xhalf_max(mx);
+                // The exponent offset follows the maximum lazily: it moves only when a logit exceeds it by
+                // more than kLazyLog2 in the log2 domain, so probabilities stay below 2^kLazyLog2 (exact in
+                // exact arithmetic: softmax is shift invariant) and the accumulators are rescaled rarely.
+                // The first tile always moves it (offset -inf; key 0 is visible to every row, so mx is finite).
+                const bool grow = mx > m_run[qb] + lazy;
+                m_new[qb] = grow ? mx : m_run[qb];
+                mc[qb] = m_new[qb] * c;
+                moved |= grow;
             }
-            float mx = -INFINITY;
+            if (__any(moved)) {                              // rescale only when some row's offset moved
 #pragma unroll
-            for (int blk = 0; blk < 2; ++blk)
+                for (int qb = 0; qb < QB; ++qb) {
+                    const float alpha = fast_exp2(m_run[qb] * c - mc[qb]);   // 1 where the maximum stayed
+                    l_run[qb] *= alpha;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[blk][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            // raw-logit maximum; the softmax scale (c > 0, log2 domain) is folded into the exponent
-            const float m_new = fmaxf(m_run, mx);            // finite: key 0 is visible to every row
-            const float mc = m_new * c;
-            if (__any(m_new != m_run)) {                     // rescale only when some row's maximum moved
-                const float alpha = fast_exp2(m_run * c - mc);
-                l_run *= alpha;
+                    for (int db = 0; db < C::ODB; ++db)
 #pragma unroll
-                for (int db = 0; db < C::ODB; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-                m_run = m_new;
+                        for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+                    m_run[qb] = m_new[qb];
+                }
             }
-            float sum = 0.f;
+            // Probabilities of this tile.  bf16: packed once into P^T operand fragments, and the row sums are
+            // taken over the values as rounded to bf16, so that numerator and denominator of the output use
+            // the same weights.  fp32: in place.
+            float sum[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) sum[qb] = 0.f;
+            typename PV<T, D, NW, QB>::Probs pr;
+            auto exps = [&](int blk, bool spread_loads) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    if constexpr (Elem<T>::kBytes == 2) {
+#pragma unroll
+                        for (int r = 0; r < 16; r += 2) {
+                            float p0 = fast_exp2(fmaf(sc[qb][blk][r], c, -mc[qb]));
+                            float p1 = fast_exp2(fmaf(sc[qb][blk][r + 1], c, -mc[qb]));
+                            if (spread_loads && qb == 0) { fetch_after_exp(blk, r, p0); fetch_after_exp(blk, r + 1, p1); }
+                            const uint32_t pk = pack_bf16x2(p0, p1);
+                            pr[qb][blk][r >> 3][(r & 7) >> 1] = pk;
+                            sum[qb] = add_bf16x2(pk, sum[qb]);
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            float p = fast_exp2(fmaf(sc[qb][blk][r], c, -mc[qb]));
+                            if (spread_loads && qb == 0) fetch_after_exp(blk, r, p);
+                            pr[qb][blk][r] = p;
+                            sum[qb] += p;
+                        }
+                    }
+                }
+            };
             if (t + 1 < my_tiles) {
                 // matrix stream: S^T of tile t+1, then P.V of tile t; vector stream: exponentials of tile t
-                qk_block<T, D, NW>(kb, 0, i, h, sw, qf, sn[0]);
-                qk_block<T, D, NW>(kb, 1, i, h, sw, qf, sn[1]);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { sc[0][r] = fast_exp2(fmaf(sc[0][r], c, -mc)); sum += sc[0][r]; }
-                PV<T, D, NW>::template run<0>(vb, i, h, sw, sc[0], o);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { sc[1][r] = fast_exp2(fmaf(sc[1][r], c, -mc)); sum += sc[1][r]; }
-                PV<T, D, NW>::template run<1>(vb, i, h, sw, sc[1], o);
-                flash_schedule<T, D>();
+                qk_block<T, D, NW, QB>(kb, 0, i, h, sw, qf, sn);
+                qk_block<T, D, NW, QB>(kb, 1, i, h, sw, qf, sn);
+                exps(0, true);
+                PV<T, D, NW, QB>::template run<0>(vb, i, h, sw, pr, o);
+                exps(1, true);
+                PV<T, D, NW, QB>::template run<1>(vb, i, h, sw, pr, o);
+                flash_schedule<T, D, QB>();
             } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { sc[0][r] = fast_exp2(fmaf(sc[0][r], c, -mc)); sum += sc[0][r]; }
-                PV<T, D, NW>::template run<0>(vb, i, h, sw, sc[0], o);
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { sc[1][r] = fast_exp2(fmaf(sc[1][r], c, -mc)); sum += sc[1][r]; }
-                PV<T, D, NW>::template run<1>(vb, i, h, sw, sc[1], o);
+                fetch_all();
+                exps(0, false);
+                PV<T, D, NW, QB>::template run<0>(vb, i, h, sw, pr, o);
+                exps(1, false);
+                PV<T, D, NW, QB>::template run<1>(vb, i, h, sw, pr, o);
             }
-            l_run += sum;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
+        } else {
+            fetch_all();
         }
         __builtin_amdgcn_s_waitcnt(0);                       // this wave's direct-to-LDS loads have landed
         __syncthreads();
@@ -393,17 +511,20 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW>::MIN_WGS)) void flash_k
         if (t + 1 < ntiles) step(t + 1, sb, sa);
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (qrow < kk) {
-        const float inv = 1.f / l_tot;
-        const int orow = out_compact ? qrow : qpos;
-        T* op = O + ((int64_t)bh * n + orow) * D;
 #pragma unroll
-        for (int db = 0; db < C::ODB; ++db)
+    for (int qb = 0; qb < QB; ++qb) {
+        const float l_tot = xhalf_sum(l_run[qb]);
+        if (qrow[qb] < kk) {
+            const float inv = 1.f / l_tot;
+            const int orow = out_compact ? qrow[qb] : qpos[qb];
+            T* op = O + ((int64_t)bh * n + orow) * D;
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-                store_out4<T>(op + 32 * db + 8 * a + 4 * h, o[db][4 * a] * inv, o[db][4 * a + 1] * inv,
-                              o[db][4 * a + 2] * inv, o[db][4 * a + 3] * inv);
+            for (int db = 0; db < C::ODB; ++db)
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+                    store_out4<T>(op + 32 * db + 8 * a + 4 * h, o[qb][db][4 * a] * inv, o[qb][db][4 * a + 1] * inv,
+                                  o[qb][db][4 * a + 2] * inv, o[qb][db][4 * a + 3] * inv);
+        }
     }
 }
 
@@ -414,14 +535,14 @@ size_t prefill_workspace_bytes(const zipvl_dims& d) {
     return 2 * (size_t)d.B * d.Hkv * npad * d.d * e;
 }
 
-template <typename T, int D, int NW>
+template <typename T, int D, int NW, int QB>
 static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const int32_t* idx, const int32_t* k,
                         float scale, int out_compact, int skip_k, const T* Kp, const T* VTp, int npad, void* O, hipStream_t st)
 {
-    using C = AttnCfg<T, D, NW>;
+    using C = AttnCfg<T, D, NW, QB>;
     static bool attr_done = false;       // raising the dynamic-LDS cap is idempotent
     if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kept_kernel<T, D, NW>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kept_kernel<T, D, NW, QB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
             return set_error(ZIPVL_EHIP, "sparse_prefill: cannot reserve %d bytes of LDS", C::LDS_BYTES);
         attr_done = true;
@@ -432,10 +553,10 @@ static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const
         const int ntq = (d.n + C::BM - 1) / C::BM;
         const int64_t blocks = (int64_t)ntq * BH;
         const int G = d.Hq / d.Hkv;
-        int ug = (4096 / NW) / (ntq * G);                   // KV heads per scheduling group (see the kernel)
+        int ug = (4096 / (NW * QB)) / (ntq * G);                  // KV heads per scheduling group (see the kernel)
         ug = ug < 1 ? 1 : ug;
         if (blocks > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
-        hipLaunchKernelGGL((flash_kept_kernel<T, D, NW>), dim3((unsigned)blocks), dim3(C::NT),
+        hipLaunchKernelGGL((flash_kept_kernel<T, D, NW, QB>), dim3((unsigned)blocks), dim3(C::NT),
             C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             skip_k ? (const T*)K : Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
             skip_k ? d.k_strides[1] : (int64_t)npad * D, VTp, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
@@ -471,9 +592,9 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     // bf16: 8 waves share every tile (half the L2 -> LDS traffic per query); fp32 keeps 4 waves
     // (its tiles are twice as large and it runs one wave per SIMD).
     if constexpr (Elem<T>::kBytes == 2)
-        return launch_flash<T, D, kFlashWavesBf16>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
+        return launch_flash<T, D, kFlashWavesBf16, kFlashBlocksBf16>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
     else
-        return launch_flash<T, D, 4>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
+        return launch_flash<T, D, 4, 1>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
 }
 
 int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims& d,

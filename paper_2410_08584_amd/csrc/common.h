@@ -72,4 +72,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// acc + lo + hi of a packed bf16 pair (the values as rounded to bf16, accumulated in fp32)
+__device__ __forceinline__ float add_bf16x2(uint32_t packed, float acc) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), ones, acc, false);
+}
+
 }  // namespace zipvl
