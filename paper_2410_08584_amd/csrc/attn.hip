@@ -13,8 +13,12 @@
 //          S^T = K Q^T and O^T = V^T P^T are taken on 32x32 MFMA tiles, so a
 //          lane owns one query column: the online-softmax statistics are
 //          per-lane scalars and only the running maximum crosses lanes (one
-//          exchange between the two half-waves per tile).  Causality is the
-//          plain lower triangle in kept-token coordinates because T is
+//          register swap between the two half-waves per tile).  The steady-state
+//          step is one basic block with an explicit instruction schedule: LDS
+//          operand reads run ahead of the MFMA that consumes them, the vector
+//          work is spread between the MFMAs, and the direct-to-LDS loads of the
+//          coming tiles are issued one at a time in its first half.  Causality is
+//          the plain lower triangle in kept-token coordinates because T is
 //          ascending.  Query rows are gathered by idx on load, output rows are
 //          scattered by idx on store, and the rows of dropped tokens between a
 //          workgroup's kept rows are cleared by that workgroup (no separate fill).
@@ -26,14 +30,11 @@
 namespace zipvl {
 
 constexpr int kBN = 64;      // keys per tile
-#ifndef ZIPVL_FLASH_WAVES_BF16
-#define ZIPVL_FLASH_WAVES_BF16 4
-#endif
-#ifndef ZIPVL_FLASH_QB_BF16
-#define ZIPVL_FLASH_QB_BF16 1
-#endif
-constexpr int kFlashWavesBf16 = ZIPVL_FLASH_WAVES_BF16;
-constexpr int kFlashBlocksBf16 = ZIPVL_FLASH_QB_BF16;
+// bf16 launch shape: 4 waves x 32 queries.  Measured alternatives: 8 waves per workgroup (half the L2 -> LDS
+// traffic per query) is 3 % slower; 64 queries per wave (QB = 2, half the LDS operand reads per MFMA) does
+// not fit the register file with the S^T double buffer and spills.
+constexpr int kFlashWavesBf16 = 4;
+constexpr int kFlashBlocksBf16 = 1;
 constexpr float kLazyLog2 = 8.f;     // slack of the running softmax offset below the running maximum (log2 domain)
 constexpr int kSchedAhead = 3;       // LDS operand reads in flight ahead of the consuming MFMA
 constexpr int kSchedValu = 4;        // vector instructions placed between two MFMAs
@@ -394,14 +395,16 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
 #pragma unroll
             for (int q = 0; q < C::NLD; ++q) load_kib_to_lds(vgt, voff[q], vl + q * NW * 1024);
         };
-        // one load after exponential r (of 16) of key block blk: K tile loads ride on block 0, V^T on block 1
+        // the step's 2 NLD loads ride on the 16 exponentials of key block 0 (the first half of the step, so
+        // that they have the second half to land): load L after exponential (2L+1) * 16 / (4 NLD)
         auto fetch_after_exp = [&](int blk, int r, float& pinned) {
+            if (blk != 0) return;
 #pragma unroll
-            for (int q = 0; q < C::NLD; ++q)
-                if (r == ((2 * q + 1) * 16) / (2 * C::NLD)) {
+            for (int L = 0; L < 2 * C::NLD; ++L)
+                if (r == ((2 * L + 1) * 16) / (4 * C::NLD)) {
                     unsigned pin = __float_as_uint(pinned);
-                    if (blk == 0) load_kib_to_lds_pinned(kgt, koff[q], kl + q * NW * 1024, pin);
-                    else load_kib_to_lds_pinned(vgt, voff[q], vl + q * NW * 1024, pin);
+                    if (L < C::NLD) load_kib_to_lds_pinned(kgt, koff[L], kl + L * NW * 1024, pin);
+                    else load_kib_to_lds_pinned(vgt, voff[L - C::NLD], vl + (L - C::NLD) * NW * 1024, pin);
                     pinned = __uint_as_float(pin);
                 }
         };
