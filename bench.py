@@ -203,6 +203,9 @@ def main():
     ap.add_argument("--gamma", type=float, default=None, help="query-mean strength of the generator (default 1.75)")
     ap.add_argument("--probes", choices=["recent", "hybrid"], default="recent",
                     help="probe rows: the last 64 positions (benchmark configs) or the paper's 64 recent + 64 random")
+    ap.add_argument("--select", choices=["per-head", "per-layer"], default="per-head",
+                    help="one important set per (batch, KV head) (benchmark configs) or one per batch element, "
+                         "selected from the head-averaged scores")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
@@ -253,11 +256,23 @@ def main():
     ws_s = torch.empty(max(256, z.workspace_bytes(z.OP_SCORE, dm, len(w.probe_pos))), dtype=torch.uint8, device=dev)
     ws_p = torch.empty(max(256, z.workspace_bytes(z.OP_SPARSE_PREFILL, dm)), dtype=torch.uint8, device=dev)
 
+    shared = args.select == "per-layer"
+    if shared:                                              # one T per batch element: scores averaged over the KV heads
+        mass_b = torch.empty((B, n), dtype=torch.float32, device=dev)
+        rank_b = torch.empty_like(mass_b)
+        idx = torch.empty((B, n), dtype=torch.int32, device=dev)
+        k = torch.empty((B,), dtype=torch.int32, device=dev)
+    tflag = z.T_PER_BATCH if shared else 0
+
     def step():
         z.zipvl_score(Q, K, w.probe_pos, w.scale, mass=mass, rank=rank, ws=ws_s)
-        z.zipvl_select(mass, rank, tau, idx=idx, k=k)
-        z.zipvl_compact_kv(K, V, idx, k, n, Kc=Kc, Vc=Vc, length=ln)
-        z.zipvl_sparse_prefill(Q, Kc4, Vc4, idx, k, w.scale, z.OUT_FULL | z.KV_ALREADY_COMPACT, O=O, ws=ws_p)
+        if shared:
+            z.zipvl_share_scores(mass, rank, B, mass_b=mass_b, rank_b=rank_b)
+            z.zipvl_select(mass_b, rank_b, tau, idx=idx, k=k)
+        else:
+            z.zipvl_select(mass, rank, tau, idx=idx, k=k)
+        z.zipvl_compact_kv(K, V, idx, k, n, tflag, Kc=Kc, Vc=Vc, length=ln)
+        z.zipvl_sparse_prefill(Q, Kc4, Vc4, idx, k, w.scale, z.OUT_FULL | z.KV_ALREADY_COMPACT | tflag, O=O, ws=ws_p)
 
     for _ in range(args.warmup):
         step()
@@ -315,6 +330,8 @@ def main():
         launch_mode = "hipgraph replay of the four C-ABI calls (outputs verified against the eager step)"
 
     k_h = k.cpu().numpy().astype(np.int64)
+    if shared:
+        k_h = np.repeat(k_h, Hkv)                            # every KV head of a batch element keeps the same k
     G = Hq // Hkv
     dense_flops = 2.0 * B * Hq * d * n * (n + 1)
     kept_flops = float(sum(G * 2.0 * d * kk * (kk + 1) for kk in k_h))
@@ -365,7 +382,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "B": B, "Hq": Hq, "Hkv": Hkv, "n": n, "d": d, "tau": tau,
-                   "probes": f"last {len(w.probe_pos)}" if args.probes == "recent" else "64 recent + 64 random", "gamma": gamma, "seed": w.seed},
+                   "probes": f"last {len(w.probe_pos)}" if args.probes == "recent" else "64 recent + 64 random", "gamma": gamma, "seed": w.seed,
+                   "important_set": "per (batch, KV head)" if not shared else "per batch element (head-averaged scores)"},
         "kept_pct": 100.0 * float(r.mean()), "kept_sq_pct": 100.0 * float((r * r).mean()),
         "k_per_unit": [int(x) for x in k_h[:16]],
         "kernels": kern,

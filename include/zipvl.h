@@ -57,6 +57,8 @@ extern "C" {
 #define ZIPVL_OUT_FULL            0  /* O is [B,Hq,n,d]; rows of dropped tokens are written as zeros */
 #define ZIPVL_OUT_COMPACT         1  /* O row i of a head is kept token i (first k rows written) */
 #define ZIPVL_KV_ALREADY_COMPACT  2  /* K,V hold the evicted cache: row i is kept token i */
+/* flag of zipvl_sparse_prefill and zipvl_compact_kv */
+#define ZIPVL_T_PER_BATCH         4  /* idx is [B,n], k is [B]: one important set serves every head of a batch element */
 
 typedef struct zipvl_dims {
     int32_t B, Hq, Hkv, n, d;
@@ -115,6 +117,19 @@ int zipvl_select(const float* mass, const float* rank, int units, int n, double 
                  int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * One important set per layer instead of one per KV head.  Paper: Algorithm 1 as written selects a
+ * single T and hands Q[T], K[T], V[T] to one attention call; this is that reading (the per-head
+ * selection is the other one).  The per-unit scores of zipvl_score are averaged over the Hkv units
+ * of each batch element, and zipvl_select then runs on B units:
+ *   mass_b[b,j] = (mass[b*Hkv+0, j] + mass[b*Hkv+1, j] + ... ) * (1/Hkv)   fp32, units added in ascending order
+ * rank_b likewise (rank and rank_b may both be NULL).  mass, rank [device] [B*Hkv, n] fp32;
+ * mass_b, rank_b [device] [B, n] fp32 (must not alias the inputs).  Pass the resulting idx [B,n], k [B]
+ * to zipvl_sparse_prefill / zipvl_compact_kv with ZIPVL_T_PER_BATCH.
+ */
+int zipvl_share_scores(const float* mass, const float* rank, int B, int Hkv, int n,
+                       float* mass_b, float* rank_b, void* stream);
+
+/*
  * Causal attention over the kept tokens only.  Paper: Section 4.2 and
  * Algorithm 1, sparse-attention step (O = Attention(Q[T], K[T], V[T])), Eq. (2)
  * restricted to T; outputs of dropped tokens are padded (with zeros here).
@@ -122,7 +137,8 @@ int zipvl_select(const float* mass, const float* rank, int units, int n, double 
  * For every query head h of unit u, with T = idx[u, 0..k[u]-1] (ascending):
  *   O[h, T_i] = sum_{j<=i} softmax_j( Q[h,T_i] . K[g,T_j] * softmax_scale ) V[g,T_j]
  * idx, k [device] as written by zipvl_select; both NULL = every token kept (dense).
- * flags: ZIPVL_OUT_FULL (default) | ZIPVL_OUT_COMPACT | ZIPVL_KV_ALREADY_COMPACT.
+ * flags: ZIPVL_OUT_FULL (default) | ZIPVL_OUT_COMPACT | ZIPVL_KV_ALREADY_COMPACT | ZIPVL_T_PER_BATCH
+ * (with ZIPVL_T_PER_BATCH, T of unit u is idx[b, 0..k[b]-1]).
  * O [device] [B,Hq,n,d] contiguous, dtype as the inputs.
  * ws [device] zipvl_workspace_bytes(ZIPVL_OP_SPARSE_PREFILL, dims, 0) bytes, 256-byte aligned.
  */
@@ -135,10 +151,11 @@ int zipvl_sparse_prefill(const void* Q, const void* K, const void* V, const zipv
  * Kc[u, i, :] = K[g, T_i, :], Vc likewise (bit copies), len[u] = k[u].
  * Kc, Vc [device] [B*Hkv, cap, d] contiguous; cap >= max k (rows beyond cap are
  * not written and len is clamped to cap).  idx,k NULL = copy all n rows.
+ * flags: 0 or ZIPVL_T_PER_BATCH (idx [B,n], k [B]; len is still written per unit).
  */
 int zipvl_compact_kv(const void* K, const void* V, const zipvl_dims* dims,
                      const int32_t* idx, const int32_t* k,
-                     void* Kc, void* Vc, int32_t cap, int32_t* len, void* stream);
+                     void* Kc, void* Vc, int32_t cap, int32_t* len, int flags, void* stream);
 
 /*
  * Decode step, cache side.  Paper: Eq. (4) / Algorithm 2 (K_out = Concat(K_in, k)).
@@ -179,7 +196,8 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
 #define ZIPVL_K_DECODE_PARTIAL  8
 #define ZIPVL_K_DECODE_COMBINE  9
 #define ZIPVL_K_SCORE_ROWFINAL 10
-#define ZIPVL_K_COUNT          11
+#define ZIPVL_K_SHARE_SCORES   11
+#define ZIPVL_K_COUNT          12
 int zipvl_timing_enable(int on);
 int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
 

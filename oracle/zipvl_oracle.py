@@ -27,7 +27,8 @@ closed form for Q=0, one-hot scores, all-rows probes against a dense softmax
 taken with another library, brute-force subset enumeration for the selection,
 tie/permutation invariance, tau=1, monotonicity in tau, uniform closed form,
 masked-dense equivalence and running-mean closed form for the kept-token
-attention, torch SDPA for dense attention, Table 2/3 ratio accounting.
+attention, head-averaged scores against the float64 mean and the single-head
+case, torch SDPA for dense attention, Table 2/3 ratio accounting.
 Parity unpinned (our own readings, checked only for self-consistency): the
 per-KV-head granularity and group averaging, the zero padding value, the 2^40
 grid, and the synthetic kept ratios.
@@ -131,6 +132,20 @@ def select(mass32: np.ndarray, rank32: Optional[np.ndarray], tau: float) -> Tupl
     return p, T.astype(np.int32)
 
 
+def share_scores(x32: np.ndarray) -> np.ndarray:
+    """One important set for every head of a layer: Algorithm 1 as written
+    selects a single T and hands Q[T], K[T], V[T] to one attention call, so
+    under that reading the per-head score vectors [U, n] of a batch element
+    are averaged into one [n].  The selection that follows is decided by
+    these bits, so the precision is fixed: fp32, heads added in ascending
+    order, then one multiplication by fp32(1/U)."""
+    x32 = np.asarray(x32, dtype=np.float32)
+    acc = x32[0].copy()
+    for u in range(1, x32.shape[0]):
+        acc = (acc + x32[u]).astype(np.float32)
+    return (acc * np.float32(1.0 / x32.shape[0])).astype(np.float32)
+
+
 def complement(n: int, T: np.ndarray) -> np.ndarray:
     """Eq. (10)."""
     keep = np.zeros(n, dtype=bool)
@@ -203,12 +218,13 @@ def decode_step(q, k_new, v_new, Kc, Vc, length, scale):
 # --------------------------------------------------------------------------
 # Whole layer for one batch element, and the ratio accounting of Tables 2 / 3
 # --------------------------------------------------------------------------
-def zipvl_prefill_layer(Q, K, V, probe_pos, tau, scale, single_vector: bool = False):
+def zipvl_prefill_layer(Q, K, V, probe_pos, tau, scale, single_vector: bool = False, shared: bool = False):
     """Algorithm 1 on given Q, K, V states of one batch element.
 
     Returns dict(mass, rank [Hkv,n] fp32, p [Hkv], T list, O [Hq,n,d],
     Kc, Vc lists).  The fp32 cast of the scores is the precision the selection
-    is defined on."""
+    is defined on.  shared=True: one T for the whole layer, selected from the
+    head-averaged scores (share_scores); p and T then repeat it per KV head."""
     Hq, n, d = Q.shape
     Hkv = K.shape[0]
     G = Hq // Hkv
@@ -216,8 +232,10 @@ def zipvl_prefill_layer(Q, K, V, probe_pos, tau, scale, single_vector: bool = Fa
     mass32, rank32 = mass.astype(np.float32), rank.astype(np.float32)
     O = np.zeros((Hq, n, V.shape[2]))
     ps, Ts, Kcs, Vcs = [], [], [], []
+    if shared:
+        p_all, T_all = select(share_scores(mass32), None if single_vector else share_scores(rank32), tau)
     for g in range(Hkv):
-        p, T = select(mass32[g], None if single_vector else rank32[g], tau)
+        p, T = (p_all, T_all) if shared else select(mass32[g], None if single_vector else rank32[g], tau)
         for h in range(g * G, (g + 1) * G):
             O[h] = kept_token_attention(Q[h], K[g], V[g], T, scale)
         Kc, Vc, _ = compact_kv(K[g], V[g], T)

@@ -11,11 +11,11 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libzipvl.so"
 
-OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT = 0, 1, 2
+OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT, T_PER_BATCH = 0, 1, 2, 4
 OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE = 1, 2, 3, 4
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
-           "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
+           "zipvl_share_scores", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
            "zipvl_timing_enable", "zipvl_timing_read")
 
 
@@ -58,7 +58,8 @@ def load_library():
     lib.zipvl_select.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_double, i32p, i32p, vp, C.c_size_t, vp]
     lib.zipvl_sparse_prefill.argtypes = [vp, vp, vp, C.POINTER(Dims), i32p, i32p, C.c_float, C.c_int,
                                          vp, vp, C.c_size_t, vp]
-    lib.zipvl_compact_kv.argtypes = [vp, vp, C.POINTER(Dims), i32p, i32p, vp, vp, C.c_int32, i32p, vp]
+    lib.zipvl_compact_kv.argtypes = [vp, vp, C.POINTER(Dims), i32p, i32p, vp, vp, C.c_int32, i32p, C.c_int, vp]
+    lib.zipvl_share_scores.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_int, f32p, f32p, vp]
     lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
     lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
                                       C.c_size_t, vp]
@@ -66,7 +67,7 @@ def load_library():
     lib.zipvl_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.zipvl_timing_enable.restype = C.c_int
     lib.zipvl_timing_read.restype = C.c_int
-    for name in ("zipvl_score", "zipvl_select", "zipvl_sparse_prefill", "zipvl_compact_kv",
+    for name in ("zipvl_score", "zipvl_select", "zipvl_share_scores", "zipvl_sparse_prefill", "zipvl_compact_kv",
                  "zipvl_kv_append", "zipvl_decode_attn"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -168,6 +169,20 @@ def zipvl_select(mass: torch.Tensor, rank: Optional[torch.Tensor], tau: float, *
     return idx, k
 
 
+def zipvl_share_scores(mass: torch.Tensor, rank: Optional[torch.Tensor], B: int, *,
+                       mass_b: Optional[torch.Tensor] = None, rank_b: Optional[torch.Tensor] = None):
+    """(mass_b, rank_b [B, n]): the per-unit scores [B*Hkv, n] averaged over the units of each batch element."""
+    lib = load_library()
+    units, n = mass.shape
+    Hkv = units // B
+    if mass_b is None:
+        mass_b = torch.empty((B, n), dtype=torch.float32, device=mass.device)
+    if rank is not None and rank_b is None:
+        rank_b = torch.empty((B, n), dtype=torch.float32, device=mass.device)
+    _check(lib.zipvl_share_scores(_ptr(mass), _ptr(rank), int(B), int(Hkv), int(n), _ptr(mass_b), _ptr(rank_b), _stream()))
+    return mass_b, rank_b
+
+
 def zipvl_sparse_prefill(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, idx: Optional[torch.Tensor],
                          k: Optional[torch.Tensor], softmax_scale: float, flags: int = OUT_FULL, *,
                          O: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
@@ -184,9 +199,9 @@ def zipvl_sparse_prefill(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, idx:
 
 
 def zipvl_compact_kv(K: torch.Tensor, V: torch.Tensor, idx: Optional[torch.Tensor], k: Optional[torch.Tensor],
-                     cap: int, *, Kc: Optional[torch.Tensor] = None, Vc: Optional[torch.Tensor] = None,
+                     cap: int, flags: int = 0, *, Kc: Optional[torch.Tensor] = None, Vc: Optional[torch.Tensor] = None,
                      length: Optional[torch.Tensor] = None):
-    """(Kc, Vc [B*Hkv, cap, d], len [B*Hkv] int32): the evicted cache."""
+    """(Kc, Vc [B*Hkv, cap, d], len [B*Hkv] int32): the evicted cache (flags: 0 or T_PER_BATCH)."""
     lib = load_library()
     dm = dims_of(None, K, V, Hq=K.shape[1])
     units = dm.B * dm.Hkv
@@ -197,7 +212,7 @@ def zipvl_compact_kv(K: torch.Tensor, V: torch.Tensor, idx: Optional[torch.Tenso
     if length is None:
         length = torch.empty((units,), dtype=torch.int32, device=K.device)
     _check(lib.zipvl_compact_kv(_ptr(K), _ptr(V), C.byref(dm), _ptr(idx), _ptr(k), _ptr(Kc), _ptr(Vc),
-                                int(cap), _ptr(length), _stream()))
+                                int(cap), _ptr(length), int(flags), _stream()))
     return Kc, Vc, length
 
 
@@ -228,7 +243,7 @@ def zipvl_decode_attn(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lengt
 
 
 KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
-           "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal")
+           "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal", "share_scores")
 
 
 def zipvl_timing_enable(on: bool) -> None:

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
     const T* __restrict__ K, const T* __restrict__ V,
     int64_t ks0, int64_t ks1, int64_t ks2, int64_t vs0, int64_t vs1, int64_t vs2,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
-    T* __restrict__ Kp, T* __restrict__ VTp, int n, int npad, int Hkv, int rows_are_kept, int skip_k)
+    T* __restrict__ Kp, T* __restrict__ VTp, int n, int npad, int Hkv, int rows_are_kept, int skip_k, int t_per_batch)
 {
     constexpr int EPF = Elem<T>::kPerFrag;
     constexpr int CPR = D / EPF;
@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
     __shared__ __attribute__((aligned(16))) T tile[kBN * LS];
     const int u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
     const int t0 = blockIdx.x * kBN;
-    int kk = kcnt ? kcnt[u] : n;
+    const int ut = t_per_batch ? b : u;                   // row of idx / k that holds this unit's T
+    int kk = kcnt ? kcnt[ut] : n;
     kk = max(0, min(kk, n));
     if (t0 >= kk) return;
     const T* Kb = K + b * ks0 + g * ks1;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
         const int r = wi / CPR, cc = wi - r * CPR, row = t0 + r;
         uintx4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
         if (row < kk) {
-            const int src = (idx && !rows_are_kept) ? idx[(int64_t)u * n + row] : row;
+            const int src = (idx && !rows_are_kept) ? idx[(int64_t)ut * n + row] : row;
             if (!skip_k) kv = load16(Kb + (int64_t)src * ks2 + cc * EPF);
             vv = load16(Vb + (int64_t)src * vs2 + cc * EPF);
         }
@@ -283,7 +284,8 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
     const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ VTp,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
-    T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped)
+    T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped,
+    int t_per_batch)
 {
     using C = AttnCfg<T, D, NW, QB>;
     constexpr int kBM = C::BM, kNT = C::NT, kRW = 32 * QB;   // queries per workgroup, threads, queries per wave
@@ -305,7 +307,8 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     const int b = u / Hkv, g = u - b * Hkv, head = g * G + hg, bh = b * Hq + head;
     const int i0 = (ntq - 1 - tile_rev) * kBM;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
-    int kk = kcnt ? kcnt[u] : n;
+    const int32_t* tidx = idx ? idx + (int64_t)(t_per_batch ? b : u) * n : nullptr;   // this unit's T
+    int kk = kcnt ? kcnt[t_per_batch ? b : u] : n;
     kk = max(0, min(kk, n));
     if (i0 >= kk) {
         if (zero_dropped && i0 == 0) zero_rows<T, D>(O, bh, n, 0, n, tid, kNT);   // nothing kept at all
@@ -317,7 +320,7 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
         int* tpos = reinterpret_cast<int*>(smem);            // [kBM + 1], dead before the first tile is staged
         for (int e = tid; e <= kBM; e += kNT) {
             const int r = i0 - 1 + e;                        // entry e: position of kept row i0 - 1 + e
-            tpos[e] = r < 0 ? -1 : (r < kk ? idx[(int64_t)u * n + r] : n);
+            tpos[e] = r < 0 ? -1 : (r < kk ? tidx[r] : n);
         }
         __syncthreads();
         if (i0 + kBM == kk) zero_rows<T, D>(O, bh, n, tpos[kBM] + 1, n, tid, kNT);   // tail after a full last tile
@@ -340,7 +343,7 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     for (int qb = 0; qb < QB; ++qb) {
         qrow[qb] = i0 + kRW * w + 32 * qb + i;
         const int qclamp = min(qrow[qb], kk - 1);
-        qpos[qb] = idx ? idx[(int64_t)u * n + qclamp] : qclamp;
+        qpos[qb] = tidx ? tidx[qclamp] : qclamp;
         const T* qp = Q + b * qs0 + head * qs1 + (int64_t)qpos[qb] * qs2;
 #pragma unroll
         for (int cc = 0; cc < C::CH; ++cc) qf[qb][cc] = load16(qp + cc * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
@@ -540,7 +543,7 @@ size_t prefill_workspace_bytes(const zipvl_dims& d) {
 
 template <typename T, int D, int NW, int QB>
 static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const int32_t* idx, const int32_t* k,
-                        float scale, int out_compact, int skip_k, const T* Kp, const T* VTp, int npad, void* O, hipStream_t st)
+                        float scale, int out_compact, int t_per_batch, int skip_k, const T* Kp, const T* VTp, int npad, void* O, hipStream_t st)
 {
     using C = AttnCfg<T, D, NW, QB>;
     static bool attr_done = false;       // raising the dynamic-LDS cap is idempotent
@@ -563,7 +566,7 @@ static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const
             C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             skip_k ? (const T*)K : Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
             skip_k ? d.k_strides[1] : (int64_t)npad * D, VTp, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
-            scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0);
+            scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0, t_per_batch);
     }
     return check_launch("flash_kept");
 }
@@ -579,6 +582,7 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     T* VTp = Kp + (size_t)units * npad * D;
     const int out_compact = (flags & ZIPVL_OUT_COMPACT) ? 1 : 0;
     const int rows_are_kept = (flags & ZIPVL_KV_ALREADY_COMPACT) ? 1 : 0;
+    const int t_per_batch = (flags & ZIPVL_T_PER_BATCH) ? 1 : 0;
 
     // An evicted cache with contiguous rows and whole 64-row tiles is read in place: only V is repacked.
     // (Rows between k and the end of the last tile may hold anything: they are masked, never summed.)
@@ -587,7 +591,7 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
         KernelTimer tm(ZIPVL_K_PACK_KV, st);
         hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kBN, units), dim3(256), 0, st,
             (const T*)K, (const T*)V, d.k_strides[0], d.k_strides[1], d.k_strides[2],
-            d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept, skip_k);
+            d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept, skip_k, t_per_batch);
     }
     int rc = check_launch("pack_kv");
     if (rc) return rc;
@@ -595,9 +599,9 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     // bf16: 8 waves share every tile (half the L2 -> LDS traffic per query); fp32 keeps 4 waves
     // (its tiles are twice as large and it runs one wave per SIMD).
     if constexpr (Elem<T>::kBytes == 2)
-        return launch_flash<T, D, kFlashWavesBf16, kFlashBlocksBf16>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
+        return launch_flash<T, D, kFlashWavesBf16, kFlashBlocksBf16>(Q, K, d, idx, k, scale, out_compact, t_per_batch, skip_k, Kp, VTp, npad, O, st);
     else
-        return launch_flash<T, D, 4, 1>(Q, K, d, idx, k, scale, out_compact, skip_k, Kp, VTp, npad, O, st);
+        return launch_flash<T, D, 4, 1>(Q, K, d, idx, k, scale, out_compact, t_per_batch, skip_k, Kp, VTp, npad, O, st);
 }
 
 int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims& d,

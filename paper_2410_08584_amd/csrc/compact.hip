@@ -14,11 +14,12 @@ __global__ __launch_bounds__(256) void compact_kv_kernel(
     int64_t vb_stride, int64_t vh_stride, int64_t vt_stride,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
     char* __restrict__ Kc, char* __restrict__ Vc, int32_t* __restrict__ len,
-    int n, int Hkv, int cap, int row_bytes)
+    int n, int Hkv, int cap, int row_bytes, int t_per_batch)
 {
     const int u = blockIdx.y;
     const int b = u / Hkv, g = u - b * Hkv;
-    int kk = kcnt ? kcnt[u] : n;
+    const int ut = t_per_batch ? b : u;                   // row of idx / k that holds this unit's T
+    int kk = kcnt ? kcnt[ut] : n;
     kk = max(0, min(min(kk, n), cap));
     if (blockIdx.x == 0 && threadIdx.x == 0) len[u] = kk;
     const int r0 = blockIdx.x * kCompactRows;
@@ -30,7 +31,7 @@ __global__ __launch_bounds__(256) void compact_kv_kernel(
     for (int w = threadIdx.x; w < kCompactRows * cpr; w += 256) {
         const int r = r0 + w / cpr, c = w - (w / cpr) * cpr;
         if (r >= kk) break;
-        const int src = idx ? idx[(int64_t)u * n + r] : r;
+        const int src = idx ? idx[(int64_t)ut * n + r] : r;
         const int64_t o = out_base + (int64_t)r * row_bytes + c * 16;
         store16(Kc + o, load16(Kb + (int64_t)src * kt_stride + c * 16));
         store16(Vc + o, load16(Vb + (int64_t)src * vt_stride + c * 16));
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(64) void kv_append_kernel(
 }
 
 int launch_compact_kv(const void* K, const void* V, const zipvl_dims& d, const int32_t* idx,
-                      const int32_t* k, void* Kc, void* Vc, int32_t cap, int32_t* len, hipStream_t st)
+                      const int32_t* k, void* Kc, void* Vc, int32_t cap, int32_t* len, int flags, hipStream_t st)
 {
     const int e = d.dtype == ZIPVL_BF16 ? 2 : 4;
     const int units = d.B * d.Hkv;
@@ -65,7 +66,7 @@ int launch_compact_kv(const void* K, const void* V, const zipvl_dims& d, const i
         (const char*)K, (const char*)V,
         d.k_strides[0] * e, d.k_strides[1] * e, d.k_strides[2] * e,
         d.v_strides[0] * e, d.v_strides[1] * e, d.v_strides[2] * e,
-        idx, k, (char*)Kc, (char*)Vc, len, d.n, d.Hkv, cap, d.d * e);
+        idx, k, (char*)Kc, (char*)Vc, len, d.n, d.Hkv, cap, d.d * e, (flags & ZIPVL_T_PER_BATCH) ? 1 : 0);
     return check_launch("compact_kv");
 }
 

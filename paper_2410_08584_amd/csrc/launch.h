@@ -29,7 +29,9 @@ int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zip
                           void* O, void* ws, hipStream_t st);
 
 int launch_compact_kv(const void* K, const void* V, const zipvl_dims& d, const int32_t* idx,
-                      const int32_t* k, void* Kc, void* Vc, int32_t cap, int32_t* len, hipStream_t st);
+                      const int32_t* k, void* Kc, void* Vc, int32_t cap, int32_t* len, int flags, hipStream_t st);
+int launch_share_scores(const float* mass, const float* rank, int B, int Hkv, int n,
+                        float* mass_b, float* rank_b, hipStream_t st);
 int launch_kv_append(void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
                      const void* v_new, const zipvl_dims& d, hipStream_t st);
 

@@ -297,4 +297,36 @@ int launch_select(const float* mass, const float* rank, int units, int n, double
     return check_launch("select");
 }
 
+// ---------------------------------------------------------------- shared selection
+// One important set per batch element: the per-unit scores are averaged over the Hkv units, units
+// added in ascending order in fp32 and the sum multiplied by fp32(1/Hkv), so that the result is a
+// fixed function of the inputs (the selection that follows is decided by these bits).
+__global__ __launch_bounds__(256) void share_scores_kernel(
+    const float* __restrict__ mass, const float* __restrict__ rank, int Hkv, int n, float inv,
+    float* __restrict__ mass_b, float* __restrict__ rank_b)
+{
+    const int b = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float* mp = mass + (int64_t)b * Hkv * n + j;
+    float a = mp[0];
+    for (int g = 1; g < Hkv; ++g) a += mp[(int64_t)g * n];
+    mass_b[(int64_t)b * n + j] = a * inv;
+    if (rank) {
+        const float* rp = rank + (int64_t)b * Hkv * n + j;
+        float r = rp[0];
+        for (int g = 1; g < Hkv; ++g) r += rp[(int64_t)g * n];
+        rank_b[(int64_t)b * n + j] = r * inv;
+    }
+}
+
+int launch_share_scores(const float* mass, const float* rank, int B, int Hkv, int n,
+                        float* mass_b, float* rank_b, hipStream_t st)
+{
+    KernelTimer tm(ZIPVL_K_SHARE_SCORES, st);
+    hipLaunchKernelGGL(share_scores_kernel, dim3((n + 255) / 256, B), dim3(256), 0, st,
+        mass, rank, Hkv, n, (float)(1.0 / Hkv), mass_b, rank_b);
+    return check_launch("share_scores");
+}
+
 }  // namespace zipvl

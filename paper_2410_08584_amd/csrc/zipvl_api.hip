@@ -153,6 +153,19 @@ int zipvl_select(const float* mass, const float* rank, int units, int n, double 
     return launch_select(mass, rank, units, n, tau, idx, k, (hipStream_t)stream);
 }
 
+int zipvl_share_scores(const float* mass, const float* rank, int B, int Hkv, int n,
+                       float* mass_b, float* rank_b, void* stream)
+{
+    const char* fn = "zipvl_share_scores";
+    if (!mass || !mass_b) return set_error(ZIPVL_EINVAL, "%s: mass and mass_b must not be NULL", fn);
+    if ((rank == nullptr) != (rank_b == nullptr)) return set_error(ZIPVL_EINVAL, "%s: rank and rank_b must both be given or both be NULL", fn);
+    if (B < 1 || Hkv < 1 || n < 1) return set_error(ZIPVL_EINVAL, "%s: B, Hkv and n must be positive (got %d, %d, %d)", fn, B, Hkv, n);
+    if ((reinterpret_cast<uintptr_t>(mass) | reinterpret_cast<uintptr_t>(rank) |
+         reinterpret_cast<uintptr_t>(mass_b) | reinterpret_cast<uintptr_t>(rank_b)) & 3u)
+        return set_error(ZIPVL_EALIGN, "%s: pointers must be 4-byte aligned", fn);
+    return launch_share_scores(mass, rank, B, Hkv, n, mass_b, rank_b, (hipStream_t)stream);
+}
+
 int zipvl_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims* dims,
                          const int32_t* idx, const int32_t* k, float softmax_scale, int flags,
                          void* O, void* ws, size_t ws_bytes, void* stream)
@@ -165,7 +178,7 @@ int zipvl_sparse_prefill(const void* Q, const void* K, const void* V, const zipv
     ZIPVL_REQUIRE_PTR(fn, V);
     ZIPVL_REQUIRE_PTR(fn, O);
     if ((idx == nullptr) != (k == nullptr)) return set_error(ZIPVL_EINVAL, "%s: idx and k must both be given or both be NULL", fn);
-    if (flags & ~(ZIPVL_OUT_COMPACT | ZIPVL_KV_ALREADY_COMPACT)) return set_error(ZIPVL_EUNSUPPORTED, "%s: unknown flags 0x%x", fn, flags);
+    if (flags & ~(ZIPVL_OUT_COMPACT | ZIPVL_KV_ALREADY_COMPACT | ZIPVL_T_PER_BATCH)) return set_error(ZIPVL_EUNSUPPORTED, "%s: unknown flags 0x%x", fn, flags);
     if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return set_error(ZIPVL_EINVAL, "%s: softmax_scale must be positive and finite", fn);
     const size_t need = prefill_workspace_bytes(*dims);
     if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
@@ -174,7 +187,7 @@ int zipvl_sparse_prefill(const void* Q, const void* K, const void* V, const zipv
 }
 
 int zipvl_compact_kv(const void* K, const void* V, const zipvl_dims* dims, const int32_t* idx,
-                     const int32_t* k, void* Kc, void* Vc, int32_t cap, int32_t* len, void* stream)
+                     const int32_t* k, void* Kc, void* Vc, int32_t cap, int32_t* len, int flags, void* stream)
 {
     const char* fn = "zipvl_compact_kv";
     int rc = check_dims(fn, dims, false, true, true);
@@ -186,7 +199,8 @@ int zipvl_compact_kv(const void* K, const void* V, const zipvl_dims* dims, const
     if (!len) return set_error(ZIPVL_EINVAL, "%s: len is NULL", fn);
     if ((idx == nullptr) != (k == nullptr)) return set_error(ZIPVL_EINVAL, "%s: idx and k must both be given or both be NULL", fn);
     if (cap < 1) return set_error(ZIPVL_EINVAL, "%s: cap = %d must be positive", fn, cap);
-    return launch_compact_kv(K, V, *dims, idx, k, Kc, Vc, cap, len, (hipStream_t)stream);
+    if (flags & ~ZIPVL_T_PER_BATCH) return set_error(ZIPVL_EUNSUPPORTED, "%s: unknown flags 0x%x", fn, flags);
+    return launch_compact_kv(K, V, *dims, idx, k, Kc, Vc, cap, len, flags, (hipStream_t)stream);
 }
 
 int zipvl_kv_append(void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,

@@ -316,6 +316,77 @@ def test_layer_with_hybrid_probe_set():
     _layer_parity(w, 0.975)
 
 
+# ------------------------------------------------------------------ one T per layer
+def test_share_scores_bit_exact():
+    say("share_scores")
+    r = np.random.Generator(np.random.PCG64(41))
+    for B, Hkv, n in ((1, 4, 18432), (3, 7, 1001), (2, 1, 77)):
+        mass = r.random((B * Hkv, n)).astype(np.float32)
+        mass /= mass.sum(axis=1, keepdims=True)
+        rank = (mass * r.random((B * Hkv, n))).astype(np.float32)
+        mb, rb = z.zipvl_share_scores(torch.from_numpy(mass).to(DEV), torch.from_numpy(rank).to(DEV), B)
+        mb2, none = z.zipvl_share_scores(torch.from_numpy(mass).to(DEV), None, B)
+        torch.cuda.synchronize()
+        assert none is None
+        for b in range(B):
+            ref_m = oz.share_scores(mass[b * Hkv:(b + 1) * Hkv])
+            assert mb[b].cpu().numpy().tobytes() == ref_m.tobytes()
+            assert mb2[b].cpu().numpy().tobytes() == ref_m.tobytes()
+            assert rb[b].cpu().numpy().tobytes() == oz.share_scores(rank[b * Hkv:(b + 1) * Hkv]).tobytes()
+
+
+@pytest.mark.parametrize("case", [dict(B=2, Hq=8, Hkv=4, n=700, d=128, dtype="bf16", seed=51, full=True),
+                                  dict(B=1, Hq=4, Hkv=4, n=333, d=64, dtype="f32", seed=52, full=True),
+                                  dict(B=1, Hq=28, Hkv=4, n=4608, d=128, dtype="bf16", seed=53, full=False)])
+def test_layer_with_one_important_set_per_batch_element(case):
+    B, Hq, Hkv, n, d, dtype = (case[key] for key in ("B", "Hq", "Hkv", "n", "d", "dtype"))
+    say(f"layer, one T per batch element: B={B} Hq={Hq} Hkv={Hkv} n={n} d={d} {dtype}")
+    G, tau = Hq // Hkv, 0.975
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=case["seed"])
+    Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
+    mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
+    mass_b, rank_b = z.zipvl_share_scores(mass, rank, B)
+    idx, k = z.zipvl_select(mass_b, rank_b, tau)
+    assert idx.shape == (B, n) and k.shape == (B,)
+    Kc, Vc, ln = z.zipvl_compact_kv(K, V, idx, k, n, z.T_PER_BATCH)
+    O = z.zipvl_sparse_prefill(Q, K, V, idx, k, w.scale, z.T_PER_BATCH)
+    # the same attention from the evicted cache, compact output rows (every case: in-place K read and repack)
+    Oc = z.zipvl_sparse_prefill(Q, Kc.view(B, Hkv, n, d), Vc.view(B, Hkv, n, d), idx, k, w.scale,
+                                z.T_PER_BATCH | z.KV_ALREADY_COMPACT | z.OUT_COMPACT)
+    torch.cuda.synchronize()
+    mass_h, rank_h = mass.cpu().numpy(), rank.cpu().numpy()
+    idx_h, k_h, ln_h = idx.cpu().numpy(), k.cpu().numpy(), ln.cpu().numpy()
+    r = np.random.Generator(np.random.PCG64(78))
+    worst = 0.0
+    for b in range(B):
+        # oracle fed the GPU's per-unit fp32 scores: same mean, same selection, exactly
+        p, T = oz.select(oz.share_scores(mass_h[b * Hkv:(b + 1) * Hkv]), oz.share_scores(rank_h[b * Hkv:(b + 1) * Hkv]), tau)
+        assert k_h[b] == p and np.array_equal(idx_h[b, :p], T), f"batch element {b}: selection differs"
+        dropped = np.setdiff1d(np.arange(n), T)
+        for g in range(Hkv):
+            u = b * Hkv + g
+            assert ln_h[u] == p
+            ko, vo, _ = oz.compact_kv(w.K[b, g], w.V[b, g], T)
+            assert Kc[u, :p].to(torch.float32).cpu().numpy().tobytes() == ko.tobytes()
+            assert Vc[u, :p].to(torch.float32).cpu().numpy().tobytes() == vo.tobytes()
+        for h in range(Hq):
+            g = h // G
+            Oh = host64(O[b, h])
+            assert not Oh[dropped].any(), "dropped rows must be zero"
+            if case["full"]:
+                ref = oz.kept_token_attention(w.Q[b, h], w.K[b, g], w.V[b, g], T, w.scale)
+                worst = max(worst, np.abs(Oh - ref).max())
+                if Oc is not None:
+                    worst = max(worst, np.abs(host64(Oc[b, h])[:p] - ref[T]).max())
+            else:
+                rows = np.unique(np.concatenate([[0, p - 1, min(127, p - 1), min(128, p - 1)], r.integers(0, p, 6)]))
+                ref = oz.kept_token_attention_rows(w.Q[b, h], w.K[b, g], w.V[b, g], T, rows, w.scale)
+                worst = max(worst, np.abs(Oh[T[rows]] - ref).max())
+                worst = max(worst, np.abs(host64(Oc[b, h])[rows] - ref).max())
+    say(f"  kept {[int(x) for x in k_h]} of {n}; worst |dO| = {worst:.3e}")
+    assert worst <= ATOL_OUT[dtype]
+
+
 def test_layer_tau_one_is_dense_attention():
     say("layer tau=1")
     w = make_custom(1, 4, 2, 320, 128, "bf16", seed=12)

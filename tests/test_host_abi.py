@@ -88,13 +88,19 @@ def test_prefill_compact_decode_reject_bad_arguments(lib):
     dm = _dims()
     sp = lib.zipvl_sparse_prefill
     assert sp(FAKE, FAKE, FAKE, C.byref(dm), FAKE, None, C.c_float(0.1), 0, FAKE, FAKE, 1 << 30, None) == -1
-    assert sp(FAKE, FAKE, FAKE, C.byref(dm), None, None, C.c_float(0.1), 8, FAKE, FAKE, 1 << 30, None) == -5
+    assert sp(FAKE, FAKE, FAKE, C.byref(dm), None, None, C.c_float(0.1), 16, FAKE, FAKE, 1 << 30, None) == -5
     assert sp(FAKE, FAKE, FAKE, C.byref(dm), None, None, C.c_float(0.1), 0, FAKE, FAKE, 8, None) == -4
     assert sp(FAKE, FAKE, FAKE, C.byref(dm), None, None, C.c_float(0.1), 0, FAKE, C.c_void_p(0x1010), 1 << 30, None) == -3
     ck = lib.zipvl_compact_kv
-    assert ck(FAKE, FAKE, C.byref(dm), None, None, FAKE, FAKE, 0, FAKE, None) == -1
-    assert ck(FAKE, FAKE, C.byref(dm), FAKE, None, FAKE, FAKE, 16, FAKE, None) == -1
-    assert ck(FAKE, FAKE, C.byref(dm), None, None, FAKE, FAKE, 16, None, None) == -1
+    assert ck(FAKE, FAKE, C.byref(dm), None, None, FAKE, FAKE, 0, FAKE, 0, None) == -1
+    assert ck(FAKE, FAKE, C.byref(dm), FAKE, None, FAKE, FAKE, 16, FAKE, 0, None) == -1
+    assert ck(FAKE, FAKE, C.byref(dm), None, None, FAKE, FAKE, 16, None, 0, None) == -1
+    assert ck(FAKE, FAKE, C.byref(dm), None, None, FAKE, FAKE, 16, FAKE, 3, None) == -5
+    sh = lib.zipvl_share_scores
+    assert sh(None, None, 1, 4, 8, FAKE, None, None) == -1
+    assert sh(FAKE, FAKE, 1, 4, 8, FAKE, None, None) == -1
+    assert sh(FAKE, None, 1, 0, 8, FAKE, None, None) == -1
+    assert sh(C.c_void_p(0x1002), None, 1, 4, 8, FAKE, None, None) == -3
     dc = lib.zipvl_decode_attn
     assert dc(FAKE, FAKE, FAKE, None, 16, C.byref(dm), C.c_float(0.1), FAKE, FAKE, 1 << 30, None) == -1
     assert dc(FAKE, FAKE, FAKE, FAKE, 16, C.byref(dm), C.c_float(0.1), FAKE, FAKE, 4, None) == -4

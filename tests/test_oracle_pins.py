@@ -292,6 +292,41 @@ def test_layer_is_the_composition_of_its_steps():
     np.testing.assert_allclose(full["O"][0], oz.dense_causal_attention(w.Q[0, 0], w.K[0, 0], w.V[0, 0], w.scale), atol=1e-13)
 
 
+def test_shared_scores_are_the_head_mean_and_reduce_to_the_single_head_case():
+    from workloads import make_custom
+    r = _rng(31)
+    x = r.random((5, 200)).astype(np.float32)
+    x /= x.sum(axis=1, keepdims=True)
+    s = oz.share_scores(x)
+    assert s.dtype == np.float32 and s.shape == (200,)
+    # the exact mean, to fp32 rounding of 5 additions and one multiplication
+    np.testing.assert_allclose(s.astype(np.float64), x.astype(np.float64).mean(axis=0), rtol=6 * 2.0 ** -24)
+    assert abs(float(s.astype(np.float64).sum()) - 1.0) < 1e-5          # still a distribution over tokens
+    # identical heads: the mean is the head (power-of-two head counts are exact)
+    one = x[:1]
+    assert oz.share_scores(np.repeat(one, 4, axis=0)).tobytes() == one[0].tobytes()
+    assert oz.share_scores(one).tobytes() == one[0].tobytes()
+    # a layer with one KV head selects the same set either way
+    w = make_custom(1, 2, 1, 96, 16, "f32", seed=4, m=16, tau=0.9)
+    a = oz.zipvl_prefill_layer(w.Q[0], w.K[0], w.V[0], w.probe_pos, 0.9, w.scale)
+    b = oz.zipvl_prefill_layer(w.Q[0], w.K[0], w.V[0], w.probe_pos, 0.9, w.scale, shared=True)
+    assert np.array_equal(a["T"][0], b["T"][0]) and np.array_equal(a["O"], b["O"])
+
+
+def test_shared_layer_uses_one_set_for_every_head():
+    from workloads import make_custom
+    w = make_custom(1, 4, 2, 96, 16, "f32", seed=3, m=16, tau=0.9)
+    out = oz.zipvl_prefill_layer(w.Q[0], w.K[0], w.V[0], w.probe_pos, 0.9, w.scale, shared=True)
+    assert out["p"][0] == out["p"][1] and np.array_equal(out["T"][0], out["T"][1])
+    # the set is the selection on the mean of the two heads' fp32 scores
+    p, T = oz.select(oz.share_scores(out["mass"]), oz.share_scores(out["rank"]), 0.9)
+    assert p == out["p"][0] and np.array_equal(T, out["T"][0])
+    # and each head's output is the kept-token attention over that set
+    for h in range(4):
+        ref = oz.kept_token_attention(w.Q[0, h], w.K[0, h // 2], w.V[0, h // 2], T, w.scale)
+        np.testing.assert_array_equal(out["O"][h], ref)
+
+
 # ------------------------------------------------------- paper's accounting
 def test_ratio_accounting_matches_tables_2_and_3():
     rows = [l.split() for l in open(os.path.join(GOLDEN, "ratio_accounting.txt")) if l.strip() and not l.startswith("#")]
