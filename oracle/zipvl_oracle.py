@@ -28,7 +28,8 @@ taken with another library, brute-force subset enumeration for the selection,
 tie/permutation invariance, tau=1, monotonicity in tau, uniform closed form,
 masked-dense equivalence and running-mean closed form for the kept-token
 attention, head-averaged scores against the float64 mean and the single-head
-case, torch SDPA for dense attention, Table 2/3 ratio accounting.
+case, the row quantiser against the nearest-grid-point definition, its
+half-step error bound and Table 3's compression ratios, torch SDPA for dense attention, Table 2/3 ratio accounting.
 Parity unpinned (our own readings, checked only for self-consistency): the
 per-KV-head granularity and group averaging, the zero padding value, the 2^40
 grid, and the synthetic kept ratios.
@@ -213,6 +214,74 @@ def decode_step(q, k_new, v_new, Kc, Vc, length, scale):
     Kc = np.concatenate([np.asarray(Kc)[:length], np.asarray(k_new)[None, :]], axis=0)
     Vc = np.concatenate([np.asarray(Vc)[:length], np.asarray(v_new)[None, :]], axis=0)
     return decode_attention(q, Kc, Vc, length + 1, scale), Kc, Vc, length + 1
+
+
+# --------------------------------------------------------------------------
+# Mixed-precision KV cache keyed by T  (Section 5.3.1: important tokens at
+# 4 bits, the others at 2 bits; the quantiser itself is not given there)
+# --------------------------------------------------------------------------
+def quantize_rows(X: np.ndarray, bits: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Uniform asymmetric quantisation of every row (one token of one KV head)
+    of X [rows, d] to `bits` bits with a per-row (scale, zero) pair kept in
+    fp16.  Reading taken here (the paper only names the bit widths):
+      zero  = fp16(min_c x_c),  scale = fp16((max_c x_c - min_c x_c) * fp32(1/(2^bits-1)))
+      code_c = clamp(rint((x_c - zero) / scale), 0, 2^bits - 1)      (0 when scale = 0)
+    all in fp32 with round-half-even, because these steps decide integers and
+    the kernel takes them in fp32.  Returns (codes uint8 [rows, d], scale, zero
+    float16 [rows])."""
+    X = np.asarray(X, dtype=np.float32)
+    qmax = np.float32(2 ** bits - 1)
+    lo, hi = X.min(axis=1), X.max(axis=1)
+    zero = lo.astype(np.float16)
+    scale = ((hi - lo) * np.float32(1.0 / float(qmax))).astype(np.float32).astype(np.float16)
+    z32, s32 = zero.astype(np.float32)[:, None], scale.astype(np.float32)[:, None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = ((X - z32).astype(np.float32) / s32).astype(np.float32)
+    t = np.where(s32 > 0, t, np.float32(0))
+    codes = np.clip(np.rint(t), 0, qmax).astype(np.uint8)
+    return codes, scale, zero
+
+
+def dequantize_rows(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray) -> np.ndarray:
+    """x^_c = zero + scale * code_c (float64)."""
+    return zero.astype(np.float64)[:, None] + scale.astype(np.float64)[:, None] * codes.astype(np.float64)
+
+
+def quantize_kv(Kg: np.ndarray, Vg: np.ndarray, T: np.ndarray, hi_bits: int = 4, lo_bits: int = 2):
+    """The mixed-precision cache of one KV head: tokens of T (ascending) at
+    hi_bits, the others (Eq. (10), ascending) at lo_bits.  Returns a dict with
+    the codes / scales / zeros of K and V for both groups."""
+    n = np.asarray(Kg).shape[0]
+    T = np.asarray(T, dtype=np.int64)
+    U = complement(n, T)
+    out = {"T": T, "U": U}
+    for name, X in (("K", Kg), ("V", Vg)):
+        X = np.asarray(X, dtype=np.float32)
+        out[name + "_hi"] = quantize_rows(X[T], hi_bits)
+        out[name + "_lo"] = quantize_rows(X[U], lo_bits) if len(U) else (np.zeros((0, X.shape[1]), np.uint8), np.zeros(0, np.float16), np.zeros(0, np.float16))
+    return out
+
+
+def decode_attention_quantized(q: np.ndarray, qc: dict, scale: float,
+                               K_tail: Optional[np.ndarray] = None, V_tail: Optional[np.ndarray] = None) -> np.ndarray:
+    """Eq. (5) over the dequantised cache: every prefill token takes part (the
+    important ones from 4-bit codes, the others from 2-bit codes), followed by
+    the rows appended during decoding, which are kept as they are."""
+    Ks = [dequantize_rows(*qc["K_hi"]), dequantize_rows(*qc["K_lo"])]
+    Vs = [dequantize_rows(*qc["V_hi"]), dequantize_rows(*qc["V_lo"])]
+    if K_tail is not None and len(K_tail):
+        Ks.append(np.asarray(K_tail, dtype=np.float64)); Vs.append(np.asarray(V_tail, dtype=np.float64))
+    Kall, Vall = np.concatenate(Ks), np.concatenate(Vs)
+    return decode_attention(q, Kall, Vall, len(Kall), scale)
+
+
+def kv_quant_compression(ratio: float, hi_bits: int = 4, lo_bits: int = 2, elems_per_group: int = 1024,
+                         param_bits: int = 32, full_bits: int = 16) -> float:
+    """Compression of a 16-bit cache when a fraction `ratio` of the tokens is
+    kept at hi_bits and the rest at lo_bits, with one (scale, zero) pair of
+    param_bits per group of elems_per_group elements (Section 5.3.1, Table 3;
+    a token-wide pair over 8 KV heads of 128 channels is 1024 elements)."""
+    return full_bits / (ratio * hi_bits + (1.0 - ratio) * lo_bits + param_bits / elems_per_group)
 
 
 # --------------------------------------------------------------------------

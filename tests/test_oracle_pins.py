@@ -327,6 +327,78 @@ def test_shared_layer_uses_one_set_for_every_head():
         np.testing.assert_array_equal(out["O"][h], ref)
 
 
+# ------------------------------------------------------- mixed-precision cache
+@pytest.mark.parametrize("bits", [2, 4])
+def test_row_quantiser_is_nearest_grid_point_with_half_step_error(bits):
+    r = _rng(60 + bits)
+    X = r.standard_normal((40, 32)).astype(np.float32)
+    X[3] = 1.25                                   # constant row: scale 0, every code 0, exact
+    codes, scale, zero = oz.quantize_rows(X, bits)
+    assert codes.dtype == np.uint8 and codes.max() <= 2 ** bits - 1
+    assert scale.dtype == np.float16 and zero.dtype == np.float16
+    s, z = scale.astype(np.float64), zero.astype(np.float64)
+    assert s[3] == 0 and not codes[3].any() and np.all(oz.dequantize_rows(codes, scale, zero)[3] == 1.25)
+    # the row minimum is code 0, the maximum the top code
+    live = s > 0
+    assert np.all(codes[np.arange(40), X.argmin(axis=1)][live] == 0)
+    assert np.all(codes[np.arange(40), X.argmax(axis=1)][live] == 2 ** bits - 1)
+    # independent definition: the code is the grid point nearest to x (checked by enumeration of the grid)
+    grid = z[:, None, None] + s[:, None, None] * np.arange(2 ** bits)[None, None, :]
+    dist = np.abs(X.astype(np.float64)[:, :, None] - grid)
+    best = dist.min(axis=2)
+    mine = np.abs(X.astype(np.float64) - oz.dequantize_rows(codes, scale, zero))
+    assert np.all(mine[live] <= best[live] + 1e-6 * s[live][:, None])
+    # hence the half-step bound (the fp16 rounding of the parameters can push the ends out by a little)
+    assert np.all(mine[live] <= 0.5 * s[live][:, None] * 1.01 + 2e-3 * np.abs(X[live]).max())
+
+
+def test_values_on_the_grid_survive_quantisation_exactly():
+    z, s = 0.5, 0.125                             # representable in fp16; row spans the whole grid
+    for bits in (2, 4):
+        q = np.arange(2 ** bits)
+        X = (z + s * np.tile(q, 3)).astype(np.float32)[None, :]
+        codes, scale, zero = oz.quantize_rows(X, bits)
+        assert float(zero[0]) == z and float(scale[0]) == s
+        assert np.array_equal(codes[0], np.tile(q, 3))
+        assert np.array_equal(oz.dequantize_rows(codes, scale, zero)[0], X[0].astype(np.float64))
+
+
+def test_mixed_precision_cache_splits_by_T_and_decodes_close_to_the_full_cache():
+    r = _rng(64)
+    n, d = 96, 32
+    K, V = r.standard_normal((n, d)).astype(np.float32), r.standard_normal((n, d)).astype(np.float32)
+    T = np.sort(r.choice(n, 30, replace=False))
+    qc = oz.quantize_kv(K, V, T)
+    assert np.array_equal(qc["U"], np.setdiff1d(np.arange(n), T))
+    assert qc["K_hi"][0].shape == (30, d) and qc["K_lo"][0].shape == (66, d)
+    assert np.array_equal(qc["K_hi"][0], oz.quantize_rows(K[T], 4)[0])
+    assert np.array_equal(qc["V_lo"][0], oz.quantize_rows(V[qc["U"]], 2)[0])
+    q = r.standard_normal(d)
+    full = oz.decode_attention(q, K, V, n, 0.2)
+    # 16-bit codes in both groups: the quantised path must reproduce the full-cache answer
+    fine = oz.decode_attention_quantized(q, oz.quantize_kv(K, V, T, 16 - 8, 16 - 8), 0.2)     # 8 bits each
+    assert np.abs(fine - full).max() < 2e-2
+    coarse = oz.decode_attention_quantized(q, qc, 0.2)
+    assert np.abs(coarse - full).max() < 0.6 and np.abs(coarse - full).max() > np.abs(fine - full).max()
+    # appended rows take part unquantised: appending the same token twice equals decode over n+2 rows
+    kt, vt = r.standard_normal((2, d)), r.standard_normal((2, d))
+    a = oz.decode_attention_quantized(q, qc, 0.2, kt, vt)
+    Kd = np.concatenate([oz.dequantize_rows(*qc["K_hi"]), oz.dequantize_rows(*qc["K_lo"]), kt])
+    Vd = np.concatenate([oz.dequantize_rows(*qc["V_hi"]), oz.dequantize_rows(*qc["V_lo"]), vt])
+    np.testing.assert_allclose(a, oz.decode_attention(q, Kd, Vd, n + 2, 0.2), atol=1e-13)
+
+
+def test_kv_compression_matches_table_3():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "kv_quant_compression.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 2
+    for ratio_pct, comp in rows:
+        got = oz.kv_quant_compression(float(ratio_pct) / 100.0)
+        assert abs(got - float(comp)) / float(comp) < 0.01, (ratio_pct, got, comp)
+    # with a pair of parameters per token and KV head (128 elements) the same split compresses less
+    assert oz.kv_quant_compression(0.286, elems_per_group=128) < oz.kv_quant_compression(0.286)
+    assert abs(oz.kv_quant_compression(1.0, param_bits=0) - 4.0) < 1e-12 and abs(oz.kv_quant_compression(0.0, param_bits=0) - 8.0) < 1e-12
+
+
 # ------------------------------------------------------- paper's accounting
 def test_ratio_accounting_matches_tables_2_and_3():
     rows = [l.split() for l in open(os.path.join(GOLDEN, "ratio_accounting.txt")) if l.strip() and not l.startswith("#")]
