@@ -52,6 +52,8 @@ extern "C" {
 #define ZIPVL_OP_SELECT         2
 #define ZIPVL_OP_SPARSE_PREFILL 3
 #define ZIPVL_OP_DECODE         4
+#define ZIPVL_OP_QUANTIZE_KV    5
+#define ZIPVL_OP_DECODE_Q       6  /* dims->n = cap_hi + cap_lo + cap_tail */
 
 /* flags of zipvl_sparse_prefill */
 #define ZIPVL_OUT_FULL            0  /* O is [B,Hq,n,d]; rows of dropped tokens are written as zeros */
@@ -178,6 +180,47 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
                       void* o, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Mixed-precision KV cache keyed by the important set.  Paper: Section 5.3.1 and Table 3 (important
+ * tokens quantised to 4 bits, the other tokens to 2 bits; nothing is evicted).  The quantiser itself is
+ * not given there; the one used is uniform, asymmetric, per row (one token of one KV head), in fp32:
+ *   zero = fp16(min_c x_c),  scale = fp16((max_c x_c - min_c x_c) * fp32(1/(2^bits - 1))),
+ *   code_c = clamp(rint((x_c - zero) / scale), 0, 2^bits - 1)   (all codes 0 when scale = 0),
+ *   dequantised value = zero + scale * code_c.
+ * One tensor (K or V) of the cache is four [device] arrays:
+ */
+typedef struct zipvl_qtensor {
+    void* hi_codes;   /* [units, cap_hi, d/2] bytes: 4-bit codes, element c in byte c/2, bits 4*(c%2)..4*(c%2)+3 */
+    void* hi_params;  /* [units, cap_hi, 2] fp16: (scale, zero) of the row */
+    void* lo_codes;   /* [units, cap_lo, d/4] bytes: 2-bit codes, element c in byte c/4, bits 2*(c%4)..2*(c%4)+1 */
+    void* lo_params;  /* [units, cap_lo, 2] fp16 */
+} zipvl_qtensor;
+
+/*
+ * Builds the cache from the prefill K, V [B,Hkv,n,d]: row i of the 4-bit group of unit u is token T_i,
+ * row i of the 2-bit group is the i-th token not in T (Eq. (10), ascending position).
+ * len_hi[u] = min(k, cap_hi), len_lo[u] = min(n - k, cap_lo) [device, units]; rows beyond a cap are not written.
+ * idx, k as written by zipvl_select (NULL = every token important); flags: 0 or ZIPVL_T_PER_BATCH.
+ * ws [device]: zipvl_workspace_bytes(ZIPVL_OP_QUANTIZE_KV, dims, 0) bytes, 4-byte aligned.  n <= 262144.
+ * Code arrays 4-byte aligned, parameter arrays 4-byte aligned.
+ */
+int zipvl_quantize_kv(const void* K, const void* V, const zipvl_dims* dims, const int32_t* idx, const int32_t* k,
+                      const zipvl_qtensor* Kq, const zipvl_qtensor* Vq, int32_t cap_hi, int32_t cap_lo,
+                      int32_t* len_hi, int32_t* len_lo, int flags, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Decode attention (Eq. (5) / Algorithm 2) over the mixed-precision cache followed by the rows appended
+ * during decoding (K_tail, V_tail [units, cap_tail, d] in the dtype of q, len_tail [units]; all three NULL =
+ * no appended rows; zipvl_kv_append maintains them):
+ *   o[h] = softmax( q[h] . [K^_hi ; K^_lo ; K_tail]^T * softmax_scale ) [V^_hi ; V^_lo ; V_tail]
+ * with K^, V^ the dequantised rows.  q, o [B*Hq, d]; G = Hq/Hkv <= 8.
+ * ws [device]: zipvl_workspace_bytes(ZIPVL_OP_DECODE_Q, dims with n = cap_hi + cap_lo + cap_tail, 0) bytes.
+ */
+int zipvl_decode_attn_q(const void* q, const zipvl_qtensor* Kq, const zipvl_qtensor* Vq,
+                        const int32_t* len_hi, const int32_t* len_lo, int32_t cap_hi, int32_t cap_lo,
+                        const void* K_tail, const void* V_tail, const int32_t* len_tail, int32_t cap_tail,
+                        const zipvl_dims* dims, float softmax_scale, void* o, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the method).  While enabled,
  * every kernel launch of the calling process is bracketed by two HIP events on
  * its own stream (up to 8192 launches are kept; later ones are not timed).
@@ -197,7 +240,10 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
 #define ZIPVL_K_DECODE_COMBINE  9
 #define ZIPVL_K_SCORE_ROWFINAL 10
 #define ZIPVL_K_SHARE_SCORES   11
-#define ZIPVL_K_COUNT          12
+#define ZIPVL_K_TOKEN_SLOTS    12
+#define ZIPVL_K_QUANTIZE_ROWS  13
+#define ZIPVL_K_DECODE_Q_PARTIAL 14
+#define ZIPVL_K_COUNT          15
 int zipvl_timing_enable(int on);
 int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
 

@@ -12,10 +12,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libzipvl.so"
 
 OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT, T_PER_BATCH = 0, 1, 2, 4
-OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE = 1, 2, 3, 4
+OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q = 1, 2, 3, 4, 5, 6
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
-           "zipvl_share_scores", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
+           "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
            "zipvl_timing_enable", "zipvl_timing_read")
 
 
@@ -29,6 +29,11 @@ class Dims(C.Structure):
     _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("n", C.c_int32), ("d", C.c_int32),
                 ("dtype", C.c_int32), ("q_strides", C.c_int64 * 3), ("k_strides", C.c_int64 * 3),
                 ("v_strides", C.c_int64 * 3)]
+
+
+class QTensor(C.Structure):
+    """zipvl_qtensor: one tensor (K or V) of the mixed-precision cache."""
+    _fields_ = [("hi_codes", C.c_void_p), ("hi_params", C.c_void_p), ("lo_codes", C.c_void_p), ("lo_params", C.c_void_p)]
 
 
 _lib = None
@@ -59,6 +64,10 @@ def load_library():
     lib.zipvl_sparse_prefill.argtypes = [vp, vp, vp, C.POINTER(Dims), i32p, i32p, C.c_float, C.c_int,
                                          vp, vp, C.c_size_t, vp]
     lib.zipvl_compact_kv.argtypes = [vp, vp, C.POINTER(Dims), i32p, i32p, vp, vp, C.c_int32, i32p, C.c_int, vp]
+    lib.zipvl_quantize_kv.argtypes = [vp, vp, C.POINTER(Dims), i32p, i32p, C.POINTER(QTensor), C.POINTER(QTensor),
+                                      C.c_int32, C.c_int32, i32p, i32p, C.c_int, vp, C.c_size_t, vp]
+    lib.zipvl_decode_attn_q.argtypes = [vp, C.POINTER(QTensor), C.POINTER(QTensor), i32p, i32p, C.c_int32, C.c_int32,
+                                        vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp, C.c_size_t, vp]
     lib.zipvl_share_scores.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_int, f32p, f32p, vp]
     lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
     lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
@@ -67,7 +76,7 @@ def load_library():
     lib.zipvl_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.zipvl_timing_enable.restype = C.c_int
     lib.zipvl_timing_read.restype = C.c_int
-    for name in ("zipvl_score", "zipvl_select", "zipvl_share_scores", "zipvl_sparse_prefill", "zipvl_compact_kv",
+    for name in ("zipvl_score", "zipvl_select", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv",
                  "zipvl_kv_append", "zipvl_decode_attn"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -242,8 +251,73 @@ def zipvl_decode_attn(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lengt
     return o
 
 
+class QCache:
+    """Device arrays of the mixed-precision cache built by zipvl_quantize_kv."""
+
+    def __init__(self, units: int, cap_hi: int, cap_lo: int, d: int, device):
+        def tensor():
+            return dict(hi_codes=torch.empty((units, cap_hi, d // 2), dtype=torch.uint8, device=device),
+                        hi_params=torch.empty((units, cap_hi, 2), dtype=torch.float16, device=device),
+                        lo_codes=torch.empty((units, cap_lo, d // 4), dtype=torch.uint8, device=device),
+                        lo_params=torch.empty((units, cap_lo, 2), dtype=torch.float16, device=device))
+        self.K, self.V = tensor(), tensor()
+        self.len_hi = torch.empty((units,), dtype=torch.int32, device=device)
+        self.len_lo = torch.empty((units,), dtype=torch.int32, device=device)
+        self.units, self.cap_hi, self.cap_lo, self.d = units, cap_hi, cap_lo, d
+
+    @staticmethod
+    def _struct(t) -> QTensor:
+        return QTensor(t["hi_codes"].data_ptr(), t["hi_params"].data_ptr(), t["lo_codes"].data_ptr(), t["lo_params"].data_ptr())
+
+    def structs(self):
+        return self._struct(self.K), self._struct(self.V)
+
+    def nbytes(self) -> int:
+        return sum(x.numel() * x.element_size() for t in (self.K, self.V) for x in t.values())
+
+
+def zipvl_quantize_kv(K: torch.Tensor, V: torch.Tensor, idx: Optional[torch.Tensor], k: Optional[torch.Tensor],
+                      cap_hi: int, cap_lo: int, flags: int = 0, *, cache: Optional[QCache] = None,
+                      ws: Optional[torch.Tensor] = None) -> QCache:
+    """Mixed-precision cache: tokens of T at 4 bits, the others at 2 bits (flags: 0 or T_PER_BATCH)."""
+    lib = load_library()
+    dm = dims_of(None, K, V, Hq=K.shape[1])
+    units = dm.B * dm.Hkv
+    if cache is None:
+        cache = QCache(units, cap_hi, cap_lo, dm.d, K.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_QUANTIZE_KV, dm), K.device)
+    kq, vq = cache.structs()
+    _check(lib.zipvl_quantize_kv(_ptr(K), _ptr(V), C.byref(dm), _ptr(idx), _ptr(k), C.byref(kq), C.byref(vq),
+                                 int(cap_hi), int(cap_lo), _ptr(cache.len_hi), _ptr(cache.len_lo), int(flags),
+                                 _ptr(ws), ws.numel(), _stream()))
+    return cache
+
+
+def zipvl_decode_attn_q(q: torch.Tensor, cache: QCache, softmax_scale: float, *, B: int, Hq: int, Hkv: int,
+                        K_tail: Optional[torch.Tensor] = None, V_tail: Optional[torch.Tensor] = None,
+                        len_tail: Optional[torch.Tensor] = None,
+                        o: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """o [B*Hq, d]: one query per head against the dequantised cache followed by the appended rows."""
+    lib = load_library()
+    cap_tail = 0 if K_tail is None else K_tail.shape[1]
+    dm = dims_of(None, None, None, B=B, Hq=Hq, Hkv=Hkv, n=cache.cap_hi + cache.cap_lo + cap_tail, d=cache.d,
+                 dtype=_dtype_code(q))
+    if o is None:
+        o = torch.empty((B * Hq, cache.d), dtype=q.dtype, device=q.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_DECODE_Q, dm), q.device)
+    kq, vq = cache.structs()
+    _check(lib.zipvl_decode_attn_q(_ptr(q), C.byref(kq), C.byref(vq), _ptr(cache.len_hi), _ptr(cache.len_lo),
+                                   int(cache.cap_hi), int(cache.cap_lo), _ptr(K_tail), _ptr(V_tail), _ptr(len_tail),
+                                   int(cap_tail), C.byref(dm), float(softmax_scale), _ptr(o), _ptr(ws), ws.numel(),
+                                   _stream()))
+    return o
+
+
 KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
-           "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal", "share_scores")
+           "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal", "share_scores",
+           "token_slots", "quantize_rows", "decode_q_partial")
 
 
 def zipvl_timing_enable(on: bool) -> None:

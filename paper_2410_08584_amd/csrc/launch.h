@@ -39,4 +39,12 @@ size_t decode_workspace_bytes(const zipvl_dims& d, int cap);
 int launch_decode_attn(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
                        const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);
 
+size_t quantize_workspace_bytes(const zipvl_dims& d);
+int launch_quantize_kv(const void* K, const void* V, const zipvl_dims& d, const int32_t* idx, const int32_t* k,
+                       const zipvl_qtensor& Kq, const zipvl_qtensor& Vq, int32_t cap_hi, int32_t cap_lo,
+                       int32_t* len_hi, int32_t* len_lo, int flags, void* ws, hipStream_t st);
+int launch_decode_attn_q(const void* q, const zipvl_qtensor& Kq, const zipvl_qtensor& Vq, const int32_t* len_hi,
+                         const int32_t* len_lo, int32_t cap_hi, int32_t cap_lo, const void* Kt, const void* Vt,
+                         const int32_t* len_t, int32_t cap_t, const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);
+
 }  // namespace zipvl

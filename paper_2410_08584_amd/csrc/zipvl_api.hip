@@ -108,6 +108,8 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m) {
         case ZIPVL_OP_SELECT: return 0;
         case ZIPVL_OP_SPARSE_PREFILL: return prefill_workspace_bytes(*dims);
         case ZIPVL_OP_DECODE: return decode_workspace_bytes(*dims, dims->n);
+        case ZIPVL_OP_QUANTIZE_KV: return quantize_workspace_bytes(*dims);
+        case ZIPVL_OP_DECODE_Q: return decode_workspace_bytes(*dims, dims->n);
         default: set_error(ZIPVL_EUNSUPPORTED, "zipvl_workspace_bytes: unknown op %d", op); return 0;
     }
 }
@@ -236,6 +238,65 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
     if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
     if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
     return launch_decode_attn(q, Kc, Vc, len, cap, *dims, softmax_scale, o, ws, (hipStream_t)stream);
+}
+
+static int check_qtensor(const char* fn, const char* what, const zipvl_qtensor* t) {
+    if (!t) return set_error(ZIPVL_EINVAL, "%s: %s is NULL", fn, what);
+    const void* ptrs[4] = {t->hi_codes, t->hi_params, t->lo_codes, t->lo_params};
+    for (const void* p : ptrs) {
+        if (!p) return set_error(ZIPVL_EINVAL, "%s: an array of %s is NULL", fn, what);
+        if (reinterpret_cast<uintptr_t>(p) & 3u) return set_error(ZIPVL_EALIGN, "%s: an array of %s is not 4-byte aligned", fn, what);
+    }
+    return ZIPVL_OK;
+}
+
+int zipvl_quantize_kv(const void* K, const void* V, const zipvl_dims* dims, const int32_t* idx, const int32_t* k,
+                      const zipvl_qtensor* Kq, const zipvl_qtensor* Vq, int32_t cap_hi, int32_t cap_lo,
+                      int32_t* len_hi, int32_t* len_lo, int flags, void* ws, size_t ws_bytes, void* stream)
+{
+    const char* fn = "zipvl_quantize_kv";
+    int rc = check_dims(fn, dims, false, true, true);
+    if (rc) return rc;
+    ZIPVL_REQUIRE_PTR(fn, K);
+    ZIPVL_REQUIRE_PTR(fn, V);
+    if ((rc = check_qtensor(fn, "Kq", Kq)) || (rc = check_qtensor(fn, "Vq", Vq))) return rc;
+    if (!len_hi || !len_lo) return set_error(ZIPVL_EINVAL, "%s: len_hi / len_lo is NULL", fn);
+    if ((idx == nullptr) != (k == nullptr)) return set_error(ZIPVL_EINVAL, "%s: idx and k must both be given or both be NULL", fn);
+    if (cap_hi < 1 || cap_lo < 1) return set_error(ZIPVL_EINVAL, "%s: cap_hi = %d and cap_lo = %d must be positive", fn, cap_hi, cap_lo);
+    if (flags & ~ZIPVL_T_PER_BATCH) return set_error(ZIPVL_EUNSUPPORTED, "%s: unknown flags 0x%x", fn, flags);
+    const size_t need = quantize_workspace_bytes(*dims);
+    if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
+    if (reinterpret_cast<uintptr_t>(ws) & 3u) return set_error(ZIPVL_EALIGN, "%s: ws is not 4-byte aligned", fn);
+    return launch_quantize_kv(K, V, *dims, idx, k, *Kq, *Vq, cap_hi, cap_lo, len_hi, len_lo, flags, ws, (hipStream_t)stream);
+}
+
+int zipvl_decode_attn_q(const void* q, const zipvl_qtensor* Kq, const zipvl_qtensor* Vq,
+                        const int32_t* len_hi, const int32_t* len_lo, int32_t cap_hi, int32_t cap_lo,
+                        const void* K_tail, const void* V_tail, const int32_t* len_tail, int32_t cap_tail,
+                        const zipvl_dims* dims, float softmax_scale, void* o, void* ws, size_t ws_bytes, void* stream)
+{
+    const char* fn = "zipvl_decode_attn_q";
+    int rc = check_dims(fn, dims, false, false, false);
+    if (rc) return rc;
+    ZIPVL_REQUIRE_PTR(fn, q);
+    ZIPVL_REQUIRE_PTR(fn, o);
+    if ((rc = check_qtensor(fn, "Kq", Kq)) || (rc = check_qtensor(fn, "Vq", Vq))) return rc;
+    if (!len_hi || !len_lo) return set_error(ZIPVL_EINVAL, "%s: len_hi / len_lo is NULL", fn);
+    if (cap_hi < 1 || cap_lo < 1) return set_error(ZIPVL_EINVAL, "%s: cap_hi = %d and cap_lo = %d must be positive", fn, cap_hi, cap_lo);
+    const bool tail = K_tail || V_tail || len_tail;
+    if (tail) {
+        if (!K_tail || !V_tail || !len_tail) return set_error(ZIPVL_EINVAL, "%s: K_tail, V_tail and len_tail must all be given or all be NULL", fn);
+        if (!aligned16(K_tail) || !aligned16(V_tail)) return set_error(ZIPVL_EALIGN, "%s: K_tail / V_tail is not 16-byte aligned", fn);
+        if (cap_tail < 1) return set_error(ZIPVL_EINVAL, "%s: cap_tail = %d must be positive", fn, cap_tail);
+    } else {
+        cap_tail = 0;
+    }
+    if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return set_error(ZIPVL_EINVAL, "%s: softmax_scale must be positive and finite", fn);
+    const size_t need = decode_workspace_bytes(*dims, cap_hi + cap_lo + cap_tail);
+    if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
+    if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
+    return launch_decode_attn_q(q, *Kq, *Vq, len_hi, len_lo, cap_hi, cap_lo, K_tail, V_tail, len_tail, cap_tail,
+                                *dims, softmax_scale, o, ws, (hipStream_t)stream);
 }
 
 int zipvl_timing_enable(int on) {

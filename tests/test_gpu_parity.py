@@ -387,6 +387,129 @@ def test_layer_with_one_important_set_per_batch_element(case):
     assert worst <= ATOL_OUT[dtype]
 
 
+# ------------------------------------------------------------------ mixed-precision cache
+def _unpack(codes: np.ndarray, bits: int) -> np.ndarray:
+    """[rows, d*bits/8] bytes -> [rows, d] codes (element c in bits [c*bits, c*bits+bits) of the row's bit string)."""
+    per = 8 // bits
+    out = np.empty((codes.shape[0], codes.shape[1] * per), dtype=np.uint8)
+    for e in range(per):
+        out[:, e::per] = (codes >> (bits * e)) & ((1 << bits) - 1)
+    return out
+
+
+def _check_qcache_against_oracle(cache, w, dtype, Ts, Hkv):
+    """Codes and fp16 parameters of every unit, bit for bit; returns the oracle caches."""
+    ref = []
+    for u, T in enumerate(Ts):
+        b, g = divmod(u, Hkv)
+        qc = oz.quantize_kv(w.K[b, g], w.V[b, g], T)
+        ref.append(qc)
+        nh, nl = len(T), w.K.shape[2] - len(T)
+        assert int(cache.len_hi[u]) == nh and int(cache.len_lo[u]) == nl
+        for name, t in (("K", cache.K), ("V", cache.V)):
+            for grp, bits, rows in (("hi", 4, nh), ("lo", 2, nl)):
+                codes, scale, zero = qc[f"{name}_{grp}"]
+                got = _unpack(t[f"{grp}_codes"][u, :rows].cpu().numpy(), bits)
+                par = t[f"{grp}_params"][u, :rows].cpu().numpy()
+                assert par[:, 0].tobytes() == scale.tobytes(), f"unit {u} {name} {grp}: scales differ"
+                assert par[:, 1].tobytes() == zero.tobytes(), f"unit {u} {name} {grp}: zeros differ"
+                bad = np.argwhere(got != codes)
+                assert len(bad) == 0, f"unit {u} {name} {grp}: {len(bad)} codes differ, first at {bad[0]}"
+    return ref
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 128), ("bf16", 64), ("f32", 64)])
+def test_quantize_kv_bit_exact_and_decode_over_it(dtype, d):
+    say(f"quantize_kv + decode_attn_q dtype={dtype} d={d}")
+    B, Hq, Hkv, n = 2, 6, 3, 333
+    G = Hq // Hkv
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=61)
+    K, V = dev(w.K, dtype), dev(w.V, dtype)
+    r = np.random.Generator(np.random.PCG64(62))
+    ks = [1, 64, 333, 200, 17, 130]                           # k = n: the 2-bit group is empty
+    idx = np.zeros((B * Hkv, n), dtype=np.int32)
+    for u in range(B * Hkv):
+        idx[u, :ks[u]] = np.sort(r.choice(n, ks[u], replace=False))
+    idx_d, k_d = torch.from_numpy(idx).to(DEV), torch.tensor(ks, dtype=torch.int32, device=DEV)
+    cache = z.zipvl_quantize_kv(K, V, idx_d, k_d, n, n)
+    torch.cuda.synchronize()
+    ref = _check_qcache_against_oracle(cache, w, dtype, [idx[u, :ks[u]] for u in range(B * Hkv)], Hkv)
+
+    # decode: one query per head over [4-bit rows | 2-bit rows | 3 appended rows]
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    qh = r.standard_normal((B * Hq, d)).astype(np.float32)
+    tail_k = r.standard_normal((3, B * Hkv, d)).astype(np.float32)
+    tail_v = r.standard_normal((3, B * Hkv, d)).astype(np.float32)
+    q = dev(qh, dtype)
+    Kt = torch.zeros((B * Hkv, 8, d), dtype=tdt, device=DEV); Vt = torch.zeros_like(Kt)
+    lt = torch.zeros((B * Hkv,), dtype=torch.int32, device=DEV)
+    o0 = z.zipvl_decode_attn_q(q, cache, w.scale, B=B, Hq=Hq, Hkv=Hkv).float().cpu().numpy().astype(np.float64)
+    for step in range(3):
+        z.zipvl_kv_append(Kt, Vt, lt, dev(tail_k[step], dtype), dev(tail_v[step], dtype), B=B, Hkv=Hkv)
+    o3 = z.zipvl_decode_attn_q(q, cache, w.scale, B=B, Hq=Hq, Hkv=Hkv, K_tail=Kt, V_tail=Vt, len_tail=lt)
+    torch.cuda.synchronize()
+    o3 = o3.float().cpu().numpy().astype(np.float64)
+    q64 = host64(q)
+    tk = host64(Kt)[:, :3]; tv = host64(Vt)[:, :3]
+    worst = 0.0
+    for bh in range(B * Hq):
+        b, h = divmod(bh, Hq)
+        u = b * Hkv + h // G
+        worst = max(worst, np.abs(o0[bh] - oz.decode_attention_quantized(q64[bh], ref[u], w.scale)).max())
+        worst = max(worst, np.abs(o3[bh] - oz.decode_attention_quantized(q64[bh], ref[u], w.scale, tk[u], tv[u])).max())
+    say(f"  worst |do| = {worst:.3e}")
+    assert worst <= ATOL_OUT[dtype]
+
+
+def test_quantize_kv_with_one_set_per_batch_element_and_without_T():
+    say("quantize_kv T_PER_BATCH / idx=NULL")
+    B, Hq, Hkv, n, d, dtype = 2, 4, 4, 1000, 128, "bf16"
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=63)
+    K, V = dev(w.K, dtype), dev(w.V, dtype)
+    r = np.random.Generator(np.random.PCG64(64))
+    ks = [411, 77]
+    idx = np.zeros((B, n), dtype=np.int32)
+    for b in range(B):
+        idx[b, :ks[b]] = np.sort(r.choice(n, ks[b], replace=False))
+    cache = z.zipvl_quantize_kv(K, V, torch.from_numpy(idx).to(DEV), torch.tensor(ks, dtype=torch.int32, device=DEV),
+                                n, n, z.T_PER_BATCH)
+    torch.cuda.synchronize()
+    _check_qcache_against_oracle(cache, w, dtype, [idx[u // Hkv, :ks[u // Hkv]] for u in range(B * Hkv)], Hkv)
+    allhi = z.zipvl_quantize_kv(K, V, None, None, n, 8)       # every token important
+    torch.cuda.synchronize()
+    _check_qcache_against_oracle(allhi, w, dtype, [np.arange(n)] * (B * Hkv), Hkv)
+
+
+def test_quantised_cache_at_stack_shape_sampled_units():
+    say("quantize_kv + decode_attn_q at B4 H32 n8192 (sampled units)")
+    from workloads import make_stack_layer_device
+    Q, K, V, probe, scale = make_stack_layer_device(7, DEV)
+    B, H, n, d = K.shape
+    mass, rank = z.zipvl_score(Q, K, probe, scale)
+    idx, k = z.zipvl_select(mass, rank, 0.975)
+    cache = z.zipvl_quantize_kv(K, V, idx, k, n, n)
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    q = torch.randn((B * H, d), generator=g, device=DEV).to(torch.bfloat16)
+    o = z.zipvl_decode_attn_q(q, cache, scale, B=B, Hq=H, Hkv=H)
+    torch.cuda.synchronize()
+    k_h, idx_h = k.cpu().numpy(), idx.cpu().numpy()
+    assert cache.len_hi.cpu().tolist() == k_h.tolist() and cache.len_lo.cpu().tolist() == (n - k_h).tolist()
+    worst = 0.0
+    for u in (0, 37, 127):
+        b, h = divmod(u, H)
+        Kh, Vh = K[b, h].float().cpu().numpy(), V[b, h].float().cpu().numpy()
+        qc = oz.quantize_kv(Kh, Vh, idx_h[u, :k_h[u]])
+        for name, t in (("K", cache.K), ("V", cache.V)):
+            assert np.array_equal(_unpack(t["hi_codes"][u, :k_h[u]].cpu().numpy(), 4), qc[name + "_hi"][0])
+            assert np.array_equal(_unpack(t["lo_codes"][u, :n - k_h[u]].cpu().numpy(), 2), qc[name + "_lo"][0])
+        refo = oz.decode_attention_quantized(host64(q[u]), qc, scale)
+        worst = max(worst, np.abs(host64(o[u]) - refo).max())
+    bits = 8.0 * cache.nbytes() / (2.0 * B * H * n * d)
+    say(f"  kept {100 * k_h.mean() / n:.1f}% at 4 bits; {bits:.2f} bits per element incl. parameters "
+        f"(compression {16 / bits:.2f}x at full capacity arrays); worst |do| = {worst:.3e}")
+    assert worst <= 2e-2
+
+
 def test_layer_tau_one_is_dense_attention():
     say("layer tau=1")
     w = make_custom(1, 4, 2, 320, 128, "bf16", seed=12)
