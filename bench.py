@@ -110,7 +110,7 @@ def run_stack(args):
     lt = torch.empty((units,), dtype=torch.int32, device=dev)
     Kt4, Vt4 = Kt.view(B, H, n, d), Vt.view(B, H, n, d)
     ws_s = ws_p = None
-    caches, fulls, kept, layer_ms = [], [], [], []
+    caches, fulls, quants, kept, layer_ms = [], [], [], [], []
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for layer in range(L):
         li = layer * (spec.layers - 1) // max(1, L - 1) if L < spec.layers else layer   # spread over the ramp
@@ -142,6 +142,13 @@ def run_stack(args):
         Kf = torch.empty((units, cap_f, d), dtype=torch.bfloat16, device=dev); Vf = torch.empty_like(Kf)
         Kf[:, :n] = K.reshape(units, n, d); Vf[:, :n] = V.reshape(units, n, d)
         fulls.append((Kf, Vf, torch.full((units,), n, dtype=torch.int32, device=dev), cap_f))
+        if args.quantized:
+            # every token stays: T at 4 bits, the others at 2 bits; rows appended while decoding go to a bf16 tail
+            qc = z.zipvl_quantize_kv(K, V, idx, k, int(k_h.max()), n - int(k_h.min()))
+            cap_t = steps_dec + 8
+            quants.append((qc, torch.empty((units, cap_t, d), dtype=torch.bfloat16, device=dev),
+                           torch.empty((units, cap_t, d), dtype=torch.bfloat16, device=dev),
+                           torch.zeros((units,), dtype=torch.int32, device=dev)))
         del Q, K, V
     kept = np.stack(kept)
     gen = torch.Generator(device=dev); gen.manual_seed(12345)
@@ -171,6 +178,29 @@ def run_stack(args):
         bytes_step = 2.0 * rows * d * e
         res[name] = {"ms_per_step": 1e3 * dt / (steps_dec - 2), "GBps": bytes_step / (dt / (steps_dec - 2)) / 1e9,
                      "GB_read_per_step": bytes_step / 1e9}
+    if args.quantized:
+        ws_q = torch.empty(max(256, z.workspace_bytes(z.OP_DECODE_Q, dmf)), dtype=torch.uint8, device=dev)
+
+        def decode_q(nsteps):
+            for _ in range(nsteps):
+                for (qc, Kt, Vt, lt_) in quants:
+                    z.zipvl_kv_append(Kt, Vt, lt_, kn, vn, B=B, Hkv=H)
+                    z.zipvl_decode_attn_q(q, qc, 1.0 / float(np.sqrt(d)), B=B, Hq=H, Hkv=H, K_tail=Kt, V_tail=Vt,
+                                          len_tail=lt_, o=o, ws=ws_q)
+        decode_q(2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        decode_q(steps_dec - 2)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        rows_hi = sum(int(qc.len_hi.sum().item()) for qc, _, _, _ in quants)
+        rows_lo = sum(int(qc.len_lo.sum().item()) for qc, _, _, _ in quants)
+        tail_rows = len(quants) * units * (2 + (steps_dec - 2 + 1) / 2.0)
+        bytes_step = 2.0 * (rows_hi * (d // 2 + 4) + rows_lo * (d // 4 + 4) + tail_rows * d * e)
+        res["quantised_4_2bit"] = {"ms_per_step": 1e3 * dt / (steps_dec - 2), "GBps": bytes_step / (dt / (steps_dec - 2)) / 1e9,
+                                   "GB_read_per_step": bytes_step / 1e9,
+                                   "bits_per_element_incl_params": 8.0 * (rows_hi * (d // 2 + 4) + rows_lo * (d // 4 + 4)) / ((rows_hi + rows_lo) * d),
+                                   "note": "all prefill tokens stay in the cache (important ones 4 bit, the others 2 bit), appended rows bf16"}
     ms_layer = float(np.mean(layer_ms))
     dense_flops = 2.0 * B * H * d * n * (n + 1)
     out = {
@@ -206,6 +236,8 @@ def main():
     ap.add_argument("--select", choices=["per-head", "per-layer"], default="per-head",
                     help="one important set per (batch, KV head) (benchmark configs) or one per batch element, "
                          "selected from the head-averaged scores")
+    ap.add_argument("--quantized", action="store_true",
+                    help="shape 5: also decode against the mixed-precision cache (important tokens 4 bit, the others 2 bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")

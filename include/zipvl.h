@@ -201,7 +201,7 @@ typedef struct zipvl_qtensor {
  * len_hi[u] = min(k, cap_hi), len_lo[u] = min(n - k, cap_lo) [device, units]; rows beyond a cap are not written.
  * idx, k as written by zipvl_select (NULL = every token important); flags: 0 or ZIPVL_T_PER_BATCH.
  * ws [device]: zipvl_workspace_bytes(ZIPVL_OP_QUANTIZE_KV, dims, 0) bytes, 4-byte aligned.  n <= 262144.
- * Code arrays 4-byte aligned, parameter arrays 4-byte aligned.
+ * All eight arrays 16-byte aligned.
  */
 int zipvl_quantize_kv(const void* K, const void* V, const zipvl_dims* dims, const int32_t* idx, const int32_t* k,
                       const zipvl_qtensor* Kq, const zipvl_qtensor* Vq, int32_t cap_hi, int32_t cap_lo,

@@ -53,8 +53,32 @@ __device__ __forceinline__ void load_queries(const T* q, int b, int g, int G, in
     }
 }
 
-// Merge the 4 row groups of every wave, then the 4 waves, and write the workgroup's partial state.
+// The 4 waves' states in red[wave][head][o[D], m, l] -> the workgroup's partial state.
 // partial layout: [(unit*G + head_in_group) * nsplit + split][D + 2]  (o[D], m, l), log2 domain
+template <int D, int GT>
+__device__ __forceinline__ void combine_waves(float (&red)[4][GT][D + 2], int u, int G, int gbase, int split, int nsplit, float* part) {
+    for (int wi = threadIdx.x; wi < GT * D; wi += 256) {
+        const int t = wi / D, dd = wi - t * D;
+        if (gbase + t >= G) continue;
+        float M = -INFINITY;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, red[ww][t][D]);
+        float acc = 0.f, lsum = 0.f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) {
+                const float a = fast_exp2(red[ww][t][D] - M);
+                acc += red[ww][t][dd] * a;
+                lsum += red[ww][t][D + 1] * a;
+            }
+        }
+        float* dst = part + (((int64_t)u * G + gbase + t) * nsplit + split) * (D + 2);
+        dst[dd] = acc;
+        if (dd == 0) { dst[D] = M; dst[D + 1] = lsum; }
+    }
+}
+
+// Merge the 4 row groups of every wave, then the 4 waves, and write the workgroup's partial state.
 template <int D, int GT>
 __device__ __forceinline__ void write_partial(float (&m)[GT], float (&l)[GT], float (&o)[GT][D / 16], float (&red)[4][GT][D + 2],
                                               int u, int G, int gbase, int split, int nsplit, float* part) {
@@ -77,31 +101,21 @@ __device__ __forceinline__ void write_partial(float (&m)[GT], float (&l)[GT], fl
         }
     }
     __syncthreads();
-    for (int wi = tid; wi < GT * D; wi += 256) {
-        const int t = wi / D, dd = wi - t * D;
-        if (gbase + t >= G) continue;
-        float M = -INFINITY;
-#pragma unroll
-        for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, red[ww][t][D]);
-        float acc = 0.f, lsum = 0.f;
-        if (M > -INFINITY) {
-#pragma unroll
-            for (int ww = 0; ww < 4; ++ww) {
-                const float a = fast_exp2(red[ww][t][D] - M);
-                acc += red[ww][t][dd] * a;
-                lsum += red[ww][t][D + 1] * a;
-            }
-        }
-        float* dst = part + (((int64_t)u * G + gbase + t) * nsplit + split) * (D + 2);
-        dst[dd] = acc;
-        if (dd == 0) { dst[D] = M; dst[D + 1] = lsum; }
-    }
+    combine_waves<D, GT>(red, u, G, gbase, split, nsplit, part);
 }
 
 // rows [r_begin, r_end) of a segment of L rows that split `split` of nsplit handles (multiples of 16 rows)
 __device__ __forceinline__ void split_range(int L, int split, int nsplit, int& r_begin, int& r_end) {
     int per = (L + nsplit - 1) / nsplit;
     per = (per + 15) & ~15;
+    r_begin = split * per;
+    r_end = min(L, r_begin + per);
+}
+
+// the same in multiples of 64 rows (16 rows per wave step)
+__device__ __forceinline__ void split_range64(int L, int split, int nsplit, int& r_begin, int& r_end) {
+    int per = (L + nsplit - 1) / nsplit;
+    per = (per + 63) & ~63;
     r_begin = split * per;
     r_end = min(L, r_begin + per);
 }
@@ -233,6 +247,236 @@ __global__ __launch_bounds__(256) void decode_q_partial_kernel(
     write_partial<D, GT>(m, l, o, red, u, G, gbase, split, nsplit, part);
 }
 
+// ---- the same, for small query groups (GT <= 2): 4 lanes per row.
+// A 4-bit row of d = 128 is 64 bytes: with 16 lanes per row a lane would hold 4 bytes and the per-row work
+// (cross-lane sums, softmax update) would dominate.  Here a lane holds d/4 consecutive elements (16 bytes of 4-bit
+// codes, 8 bytes of 2-bit codes), a wave covers 16 rows per step, and the arithmetic runs on the codes:
+//   q . (zero + scale * code) = zero * sum(q) + scale * (q . code),
+//   sum_j p_j (zero_j + scale_j * code_j) = sum_j p_j zero_j + sum_j (p_j scale_j) code_j,
+// i.e. one conversion and one FMA per element and side.  The softmax offset follows the running maximum lazily
+// (moves only when exceeded by 2^kDecLazyLog2), so the accumulators are rescaled on few rows.
+constexpr float kDecLazyLog2 = 8.f;
+
+// sum over the 4 lanes of a quad (lanes 4i .. 4i+3), result in all four, by two in-register lane permutes
+__device__ __forceinline__ float quad_sum(float v) {
+    int x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    return v;
+}
+
+// the NB-byte code string of one lane -> EPL = NB * 8 / BITS floats (codes as numbers), element e at bits [e*BITS, ..)
+template <int BITS, int NW>
+__device__ __forceinline__ void codes_to_floats(const uint32_t (&w)[NW], float (&f)[NW * 32 / BITS]) {
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        if constexpr (BITS == 4) {
+            const uint32_t ev = w[i] & 0x0F0F0F0Fu, od = (w[i] >> 4) & 0x0F0F0F0Fu;   // codes 0,2,4,6 / 1,3,5,7 as bytes
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                f[8 * i + 2 * b] = (float)((ev >> (8 * b)) & 0xFFu);
+                f[8 * i + 2 * b + 1] = (float)((od >> (8 * b)) & 0xFFu);
+            }
+        } else {
+#pragma unroll
+            for (int sft = 0; sft < 4; ++sft) {
+                const uint32_t t = (w[i] >> (2 * sft)) & 0x03030303u;                  // codes sft, sft+4, sft+8, sft+12 as bytes
+#pragma unroll
+                for (int b = 0; b < 4; ++b) f[16 * i + 4 * b + sft] = (float)((t >> (8 * b)) & 0xFFu);
+            }
+        }
+    }
+}
+
+template <int NW> __device__ __forceinline__ void load_words(const uint8_t* p, uint32_t (&w)[NW]);
+template <> __device__ __forceinline__ void load_words<4>(const uint8_t* p, uint32_t (&w)[4]) {
+    const uintx4 v = load16(p); w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+}
+template <> __device__ __forceinline__ void load_words<2>(const uint8_t* p, uint32_t (&w)[2]) {
+    const uintx2 v = *reinterpret_cast<const uintx2*>(p); w[0] = v[0]; w[1] = v[1];
+}
+template <> __device__ __forceinline__ void load_words<1>(const uint8_t* p, uint32_t (&w)[1]) {
+    w[0] = *reinterpret_cast<const uint32_t*>(p);
+}
+
+template <typename T, int D, int GT>
+__global__ __launch_bounds__(256) void decode_q4_partial_kernel(
+    const T* __restrict__ q, QTensor Kq, QTensor Vq, const int32_t* __restrict__ len_hi, const int32_t* __restrict__ len_lo,
+    int cap_hi, int cap_lo, const T* __restrict__ Kt, const T* __restrict__ Vt, const int32_t* __restrict__ len_t, int cap_t,
+    int Hq, int Hkv, int gbase, float c, float* __restrict__ part, int nsplit)
+{
+    constexpr int EPL = D / 4;                               // elements per lane
+    __shared__ float red[4][GT][D + 2];
+    const int G = Hq / Hkv;
+    const int split = blockIdx.x, u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, sub = lane & 3, rg = lane >> 2;   // 16 rows per wave step
+    float qv[GT][EPL], qsum[GT];
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+        const int hh = gbase + t;
+        float part_sum = 0.f;
+#pragma unroll
+        for (int e8 = 0; e8 < EPL / 8; ++e8) {
+            float f[8];
+            if (hh < G) RowChunk<T, 8>::load(q + ((int64_t)(b * Hq + g * G + hh)) * D + sub * EPL + 8 * e8, f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { qv[t][8 * e8 + e] = hh < G ? f[e] * c : 0.f; part_sum += qv[t][8 * e8 + e]; }
+        }
+        qsum[t] = quad_sum(part_sum);                        // sum over the whole row of the scaled query
+    }
+    float m[GT], l[GT], zacc[GT], o[GT][EPL];
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+        m[t] = -INFINITY; l[t] = 0.f; zacc[t] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[t][e] = 0.f;
+    }
+    // one cached row: kd[t] = q_t . (this lane's K codes), score = kz * qsum + ks * sum over lanes of kd; then
+    // o += (p * vs) * (V codes), zacc += p * vz
+    auto attend = [&](bool valid, const float (&kc)[EPL], float ks, float kz, const float (&vc)[EPL], float vs, float vz) {
+#pragma unroll
+        for (int t = 0; t < GT; ++t) {
+            float dsum = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) dsum = fmaf(qv[t][e], kc[e], dsum);
+            dsum = quad_sum(dsum);
+            const float sc = valid ? fmaf(ks, dsum, kz * qsum[t]) : -INFINITY;
+            const bool grow = sc > m[t] + kDecLazyLog2;
+            if (__any(grow)) {
+                const float m_new = grow ? sc : m[t];
+                const float a = grow ? fast_exp2(m[t] - m_new) : 1.f;   // 0 on a row group's first row (m = -inf)
+                l[t] *= a; zacc[t] *= a;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) o[t][e] *= a;
+                m[t] = m_new;
+            }
+            const float p = valid ? fast_exp2(sc - m[t]) : 0.f;
+            l[t] += p;
+            zacc[t] = fmaf(p, vz, zacc[t]);
+            const float pv = p * vs;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[t][e] = fmaf(pv, vc[e], o[t][e]);
+        }
+    };
+    auto unpack_params = [](uint32_t v, float& scale, float& zero) {
+        scale = (float)__builtin_bit_cast(_Float16, (uint16_t)(v & 0xFFFFu));
+        zero = (float)__builtin_bit_cast(_Float16, (uint16_t)(v >> 16));
+    };
+    int r_begin, r_end;
+    {   // important tokens, 4 bits
+        constexpr int NW = EPL * 4 / 32;
+        const int L = max(0, min(len_hi[u], cap_hi));
+        split_range64(L, split, nsplit, r_begin, r_end);
+        const int64_t base = (int64_t)u * cap_hi;
+        // the loads of the next 16 rows are issued before the current ones are consumed
+        uint32_t kw[NW], vw[NW], kp, vp;
+        auto fetch = [&](int r, uint32_t (&kw_)[NW], uint32_t (&vw_)[NW], uint32_t& kp_, uint32_t& vp_) {
+            const int64_t row = base + (r < r_end ? r : r_begin);
+            load_words<NW>(Kq.hi_codes + row * (D / 2) + sub * (NW * 4), kw_);
+            load_words<NW>(Vq.hi_codes + row * (D / 2) + sub * (NW * 4), vw_);
+            kp_ = Kq.hi_params[row];
+            vp_ = Vq.hi_params[row];
+        };
+        int r = r_begin + w * 16 + rg;
+        if (r - rg - w * 16 < r_end) fetch(r, kw, vw, kp, vp);
+        for (; r - rg - w * 16 < r_end; r += 64) {
+            const bool valid = r < r_end;
+            uint32_t kw2[NW], vw2[NW], kp2 = 0, vp2 = 0;
+            const bool more = r + 64 - rg - w * 16 < r_end;
+            if (more) fetch(r + 64, kw2, vw2, kp2, vp2);
+            float ks, kz, vs, vz, kc[EPL], vc[EPL];
+            unpack_params(kp, ks, kz);
+            unpack_params(vp, vs, vz);
+            codes_to_floats<4, NW>(kw, kc);
+            codes_to_floats<4, NW>(vw, vc);
+            attend(valid, kc, ks, kz, vc, vs, vz);
+            if (more) {
+#pragma unroll
+                for (int i = 0; i < NW; ++i) { kw[i] = kw2[i]; vw[i] = vw2[i]; }
+                kp = kp2; vp = vp2;
+            }
+        }
+    }
+    {   // the other tokens, 2 bits
+        constexpr int NW = EPL * 2 / 32;
+        const int L = max(0, min(len_lo[u], cap_lo));
+        split_range64(L, split, nsplit, r_begin, r_end);
+        const int64_t base = (int64_t)u * cap_lo;
+        // the loads of the next 16 rows are issued before the current ones are consumed
+        uint32_t kw[NW], vw[NW], kp, vp;
+        auto fetch = [&](int r, uint32_t (&kw_)[NW], uint32_t (&vw_)[NW], uint32_t& kp_, uint32_t& vp_) {
+            const int64_t row = base + (r < r_end ? r : r_begin);
+            load_words<NW>(Kq.lo_codes + row * (D / 4) + sub * (NW * 4), kw_);
+            load_words<NW>(Vq.lo_codes + row * (D / 4) + sub * (NW * 4), vw_);
+            kp_ = Kq.lo_params[row];
+            vp_ = Vq.lo_params[row];
+        };
+        int r = r_begin + w * 16 + rg;
+        if (r - rg - w * 16 < r_end) fetch(r, kw, vw, kp, vp);
+        for (; r - rg - w * 16 < r_end; r += 64) {
+            const bool valid = r < r_end;
+            uint32_t kw2[NW], vw2[NW], kp2 = 0, vp2 = 0;
+            const bool more = r + 64 - rg - w * 16 < r_end;
+            if (more) fetch(r + 64, kw2, vw2, kp2, vp2);
+            float ks, kz, vs, vz, kc[EPL], vc[EPL];
+            unpack_params(kp, ks, kz);
+            unpack_params(vp, vs, vz);
+            codes_to_floats<2, NW>(kw, kc);
+            codes_to_floats<2, NW>(vw, vc);
+            attend(valid, kc, ks, kz, vc, vs, vz);
+            if (more) {
+#pragma unroll
+                for (int i = 0; i < NW; ++i) { kw[i] = kw2[i]; vw[i] = vw2[i]; }
+                kp = kp2; vp = vp2;
+            }
+        }
+    }
+    if (Kt) {   // rows appended during decoding, as stored: "codes" are the values, scale 1, zero 0
+        const int L = max(0, min(len_t[u], cap_t));
+        split_range64(L, split, nsplit, r_begin, r_end);
+        const T* Kb = Kt + (int64_t)u * cap_t * D + sub * EPL;
+        const T* Vb = Vt + (int64_t)u * cap_t * D + sub * EPL;
+        for (int r = r_begin + w * 16 + rg; r - rg - w * 16 < r_end; r += 64) {
+            const bool valid = r < r_end;
+            const int rr = valid ? r : r_begin;
+            float kc[EPL], vc[EPL];
+#pragma unroll
+            for (int e8 = 0; e8 < EPL / 8; ++e8) {
+                float f[8];
+                RowChunk<T, 8>::load(Kb + (int64_t)rr * D + 8 * e8, f);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) kc[8 * e8 + e] = f[e];
+                RowChunk<T, 8>::load(Vb + (int64_t)rr * D + 8 * e8, f);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vc[8 * e8 + e] = f[e];
+            }
+            attend(valid, kc, 1.f, 0.f, vc, 1.f, 0.f);
+        }
+    }
+    // fold the zero-point sums into the outputs, merge the 16 row groups of the wave, then the 4 waves
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[t][e] += zacc[t];
+#pragma unroll
+        for (int off = 4; off <= 32; off <<= 1) {
+            const float m2 = __shfl_xor(m[t], off), l2 = __shfl_xor(l[t], off);
+            float o2[EPL];
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o2[e] = __shfl_xor(o[t][e], off);
+            merge_state<EPL>(m[t], l[t], o[t], m2, l2, o2);
+        }
+        if (rg == 0) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) red[w][t][sub * EPL + e] = o[t][e];
+            if (sub == 0) { red[w][t][D] = m[t]; red[w][t][D + 1] = l[t]; }
+        }
+    }
+    __syncthreads();
+    combine_waves<D, GT>(red, u, G, gbase, split, nsplit, part);
+}
+
 template <typename T> __device__ __forceinline__ T to_out(float x);
 template <> __device__ __forceinline__ float to_out<float>(float x) { return x; }
 template <> __device__ __forceinline__ __bf16 to_out<__bf16>(float x) { return (__bf16)x; }
@@ -309,7 +553,15 @@ static int launch_decode_q_t(const void* q, const zipvl_qtensor& Kq, const zipvl
     for (int gb = 0; gb < G; gb += 8) {
         const int rem = G - gb;
         KernelTimer tm(ZIPVL_K_DECODE_Q_PARTIAL, st);
-        if (rem >= 5) ZIPVL_DECQ(8, gb);
+        if (G <= 2) {
+            if (rem == 2)
+                hipLaunchKernelGGL((decode_q4_partial_kernel<T, D, 2>), grid, dim3(256), 0, st, (const T*)q, kq, vq,
+                    len_hi, len_lo, cap_hi, cap_lo, (const T*)Kt, (const T*)Vt, len_t, cap_t, d.Hq, d.Hkv, gb, c, (float*)ws, nsplit);
+            else
+                hipLaunchKernelGGL((decode_q4_partial_kernel<T, D, 1>), grid, dim3(256), 0, st, (const T*)q, kq, vq,
+                    len_hi, len_lo, cap_hi, cap_lo, (const T*)Kt, (const T*)Vt, len_t, cap_t, d.Hq, d.Hkv, gb, c, (float*)ws, nsplit);
+        }
+        else if (rem >= 5) ZIPVL_DECQ(8, gb);
         else if (rem >= 3) ZIPVL_DECQ(4, gb);
         else if (rem == 2) ZIPVL_DECQ(2, gb);
         else ZIPVL_DECQ(1, gb);

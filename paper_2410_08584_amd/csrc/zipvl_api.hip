@@ -245,7 +245,7 @@ static int check_qtensor(const char* fn, const char* what, const zipvl_qtensor* 
     const void* ptrs[4] = {t->hi_codes, t->hi_params, t->lo_codes, t->lo_params};
     for (const void* p : ptrs) {
         if (!p) return set_error(ZIPVL_EINVAL, "%s: an array of %s is NULL", fn, what);
-        if (reinterpret_cast<uintptr_t>(p) & 3u) return set_error(ZIPVL_EALIGN, "%s: an array of %s is not 4-byte aligned", fn, what);
+        if (!aligned16(p)) return set_error(ZIPVL_EALIGN, "%s: an array of %s is not 16-byte aligned", fn, what);
     }
     return ZIPVL_OK;
 }

@@ -461,6 +461,31 @@ def test_quantize_kv_bit_exact_and_decode_over_it(dtype, d):
     assert worst <= ATOL_OUT[dtype]
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2), (14, 2)])
+def test_decode_over_quantised_cache_for_every_group_size(Hq, Hkv):
+    say(f"decode_attn_q Hq={Hq} Hkv={Hkv}")
+    B, n, d, dtype = 1, 700, 128, "bf16"
+    G = Hq // Hkv
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=65)
+    K, V = dev(w.K, dtype), dev(w.V, dtype)
+    r = np.random.Generator(np.random.PCG64(66))
+    ks = [r.integers(1, n) for _ in range(Hkv)]
+    idx = np.zeros((Hkv, n), dtype=np.int32)
+    for u in range(Hkv):
+        idx[u, :ks[u]] = np.sort(r.choice(n, ks[u], replace=False))
+    cache = z.zipvl_quantize_kv(K, V, torch.from_numpy(idx).to(DEV), torch.tensor(ks, dtype=torch.int32, device=DEV), n, n)
+    q = dev(r.standard_normal((Hq, d)).astype(np.float32), dtype)
+    o = z.zipvl_decode_attn_q(q, cache, w.scale, B=B, Hq=Hq, Hkv=Hkv)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for h in range(Hq):
+        u = h // G
+        qc = oz.quantize_kv(w.K[0, u], w.V[0, u], idx[u, :ks[u]])
+        worst = max(worst, np.abs(host64(o[h]) - oz.decode_attention_quantized(host64(q[h]), qc, w.scale)).max())
+    say(f"  worst |do| = {worst:.3e}")
+    assert worst <= 2e-2
+
+
 def test_quantize_kv_with_one_set_per_batch_element_and_without_T():
     say("quantize_kv T_PER_BATCH / idx=NULL")
     B, Hq, Hkv, n, d, dtype = 2, 4, 4, 1000, 128, "bf16"
