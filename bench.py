@@ -233,6 +233,9 @@ def main():
     ap.add_argument("--gamma", type=float, default=None, help="query-mean strength of the generator (default 1.75)")
     ap.add_argument("--probes", choices=["recent", "hybrid"], default="recent",
                     help="probe rows: the last 64 positions (benchmark configs) or the paper's 64 recent + 64 random")
+    ap.add_argument("--score", choices=["probes", "all-rows"], default="probes",
+                    help="token scores from the probe rows (the method) or from every row of the attention matrix "
+                         "(exact Eq. (6)/(8): the accuracy reference, two more passes over the causal half of Q K^T)")
     ap.add_argument("--select", choices=["per-head", "per-layer"], default="per-head",
                     help="one important set per (batch, KV head) (benchmark configs) or one per batch element, "
                          "selected from the head-averaged scores")
@@ -296,8 +299,15 @@ def main():
         k = torch.empty((B,), dtype=torch.int32, device=dev)
     tflag = z.T_PER_BATCH if shared else 0
 
+    exact = args.score == "all-rows"
+    if exact:
+        ws_s = torch.empty(max(256, z.workspace_bytes(z.OP_SCORE_ALL_ROWS, dm)), dtype=torch.uint8, device=dev)
+
     def step():
-        z.zipvl_score(Q, K, w.probe_pos, w.scale, mass=mass, rank=rank, ws=ws_s)
+        if exact:
+            z.zipvl_score_all_rows(Q, K, w.scale, mass=mass, rank=rank, ws=ws_s)
+        else:
+            z.zipvl_score(Q, K, w.probe_pos, w.scale, mass=mass, rank=rank, ws=ws_s)
         if shared:
             z.zipvl_share_scores(mass, rank, B, mass_b=mass_b, rank_b=rank_b)
             z.zipvl_select(mass_b, rank_b, tau, idx=idx, k=k)
@@ -414,7 +424,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": spec.name, "B": B, "Hq": Hq, "Hkv": Hkv, "n": n, "d": d, "tau": tau,
-                   "probes": f"last {len(w.probe_pos)}" if args.probes == "recent" else "64 recent + 64 random", "gamma": gamma, "seed": w.seed,
+                   "probes": ("every row (exact scores)" if exact else f"last {len(w.probe_pos)}" if args.probes == "recent" else "64 recent + 64 random"), "gamma": gamma, "seed": w.seed,
                    "important_set": "per (batch, KV head)" if not shared else "per batch element (head-averaged scores)"},
         "kept_pct": 100.0 * float(r.mean()), "kept_sq_pct": 100.0 * float((r * r).mean()),
         "k_per_unit": [int(x) for x in k_h[:16]],

@@ -54,6 +54,7 @@ extern "C" {
 #define ZIPVL_OP_DECODE         4
 #define ZIPVL_OP_QUANTIZE_KV    5
 #define ZIPVL_OP_DECODE_Q       6  /* dims->n = cap_hi + cap_lo + cap_tail */
+#define ZIPVL_OP_SCORE_ALL_ROWS 7
 
 /* flags of zipvl_sparse_prefill */
 #define ZIPVL_OUT_FULL            0  /* O is [B,Hq,n,d]; rows of dropped tokens are written as zeros */
@@ -97,6 +98,19 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m);
 int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims,
                 const int32_t* probe_pos, int m, float softmax_scale,
                 float* mass, float* rank, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The same scores from EVERY row of the attention matrix instead of m probe rows.  Paper: Eq. (6) and
+ * Eq. (8) as written in Section 4.1 (the probe rows of the supplementary material approximate these);
+ * supplementary Table A, row "all".  A (n x n per head) is never stored; the cost is two passes over the
+ * causal half of Q K^T.
+ *   A[i,j] = softmax_j( Q[h,i] . K[g,j] * softmax_scale ), keys j > i masked
+ *   a_j = sum_{i >= j} A[i,j];  mass[u,j] = group mean of a_j / n;  rank[u,j] = group mean of a_j / (n - j)
+ * Q, K, mass, rank as for zipvl_score (rank may be NULL).
+ * ws [device]: zipvl_workspace_bytes(ZIPVL_OP_SCORE_ALL_ROWS, dims, 0) bytes, 16-byte aligned.
+ */
+int zipvl_score_all_rows(const void* Q, const void* K, const zipvl_dims* dims, float softmax_scale,
+                         float* mass, float* rank, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * How many tokens to keep and which.  Paper: Eq. (7) (smallest count whose
@@ -243,7 +257,9 @@ int zipvl_decode_attn_q(const void* q, const zipvl_qtensor* Kq, const zipvl_qten
 #define ZIPVL_K_TOKEN_SLOTS    12
 #define ZIPVL_K_QUANTIZE_ROWS  13
 #define ZIPVL_K_DECODE_Q_PARTIAL 14
-#define ZIPVL_K_COUNT          15
+#define ZIPVL_K_ALLROWS_LSE    15
+#define ZIPVL_K_ALLROWS_COLSUM 16
+#define ZIPVL_K_COUNT          17
 int zipvl_timing_enable(int on);
 int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
 

@@ -12,10 +12,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libzipvl.so"
 
 OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT, T_PER_BATCH = 0, 1, 2, 4
-OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q = 1, 2, 3, 4, 5, 6
+OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q, OP_SCORE_ALL_ROWS = 1, 2, 3, 4, 5, 6, 7
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
-           "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
+           "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
            "zipvl_timing_enable", "zipvl_timing_read")
 
 
@@ -68,6 +68,7 @@ def load_library():
                                       C.c_int32, C.c_int32, i32p, i32p, C.c_int, vp, C.c_size_t, vp]
     lib.zipvl_decode_attn_q.argtypes = [vp, C.POINTER(QTensor), C.POINTER(QTensor), i32p, i32p, C.c_int32, C.c_int32,
                                         vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp, C.c_size_t, vp]
+    lib.zipvl_score_all_rows.argtypes = [vp, vp, C.POINTER(Dims), C.c_float, f32p, f32p, vp, C.c_size_t, vp]
     lib.zipvl_share_scores.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_int, f32p, f32p, vp]
     lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
     lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
@@ -76,7 +77,7 @@ def load_library():
     lib.zipvl_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.zipvl_timing_enable.restype = C.c_int
     lib.zipvl_timing_read.restype = C.c_int
-    for name in ("zipvl_score", "zipvl_select", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv",
+    for name in ("zipvl_score", "zipvl_score_all_rows", "zipvl_select", "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv",
                  "zipvl_kv_append", "zipvl_decode_attn"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -176,6 +177,24 @@ def zipvl_select(mass: torch.Tensor, rank: Optional[torch.Tensor], tau: float, *
         k = torch.empty((units,), dtype=torch.int32, device=mass.device)
     _check(lib.zipvl_select(_ptr(mass), _ptr(rank), units, n, float(tau), _ptr(idx), _ptr(k), None, 0, _stream()))
     return idx, k
+
+
+def zipvl_score_all_rows(Q: torch.Tensor, K: torch.Tensor, softmax_scale: float, *,
+                         mass: Optional[torch.Tensor] = None, rank: Optional[torch.Tensor] = None,
+                         ws: Optional[torch.Tensor] = None, want_rank: bool = True):
+    """(mass, rank) [B*Hkv, n] fp32 from every row of the attention matrix (exact Eq. (6) / Eq. (8))."""
+    lib = load_library()
+    dm = dims_of(Q, K)
+    units = dm.B * dm.Hkv
+    if mass is None:
+        mass = torch.empty((units, dm.n), dtype=torch.float32, device=Q.device)
+    if rank is None and want_rank:
+        rank = torch.empty((units, dm.n), dtype=torch.float32, device=Q.device)
+    if ws is None:
+        ws = _workspace(workspace_bytes(OP_SCORE_ALL_ROWS, dm), Q.device)
+    _check(lib.zipvl_score_all_rows(_ptr(Q), _ptr(K), C.byref(dm), float(softmax_scale), _ptr(mass), _ptr(rank),
+                                    _ptr(ws), ws.numel(), _stream()))
+    return mass, rank
 
 
 def zipvl_share_scores(mass: torch.Tensor, rank: Optional[torch.Tensor], B: int, *,
@@ -317,7 +336,7 @@ def zipvl_decode_attn_q(q: torch.Tensor, cache: QCache, softmax_scale: float, *,
 
 KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
            "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal", "share_scores",
-           "token_slots", "quantize_rows", "decode_q_partial")
+           "token_slots", "quantize_rows", "decode_q_partial", "allrows_lse", "allrows_colsum")
 
 
 def zipvl_timing_enable(on: bool) -> None:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzipvl.so")
-SOURCES = ["zipvl_api.hip", "score.hip", "select.hip", "attn.hip", "compact.hip", "decode.hip", "quant.hip"]
+SOURCES = ["zipvl_api.hip", "score.hip", "select.hip", "attn.hip", "compact.hip", "decode.hip", "quant.hip", "allrows.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
@@ -35,7 +35,7 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objs, "-o", LIB]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -110,6 +110,7 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m) {
         case ZIPVL_OP_DECODE: return decode_workspace_bytes(*dims, dims->n);
         case ZIPVL_OP_QUANTIZE_KV: return quantize_workspace_bytes(*dims);
         case ZIPVL_OP_DECODE_Q: return decode_workspace_bytes(*dims, dims->n);
+        case ZIPVL_OP_SCORE_ALL_ROWS: return allrows_workspace_bytes(*dims);
         default: set_error(ZIPVL_EUNSUPPORTED, "zipvl_workspace_bytes: unknown op %d", op); return 0;
     }
 }
@@ -138,6 +139,23 @@ int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims, const int3
     if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
     if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
     return launch_score(Q, K, *dims, probe_pos, m, softmax_scale, mass, rank, ws, (hipStream_t)stream);
+}
+
+int zipvl_score_all_rows(const void* Q, const void* K, const zipvl_dims* dims, float softmax_scale,
+                         float* mass, float* rank, void* ws, size_t ws_bytes, void* stream)
+{
+    const char* fn = "zipvl_score_all_rows";
+    int rc = check_dims(fn, dims, true, true, false);
+    if (rc) return rc;
+    ZIPVL_REQUIRE_PTR(fn, Q);
+    ZIPVL_REQUIRE_PTR(fn, K);
+    ZIPVL_REQUIRE_PTR(fn, mass);
+    if (rank && !aligned16(rank)) return set_error(ZIPVL_EALIGN, "%s: rank is not 16-byte aligned", fn);
+    if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return set_error(ZIPVL_EINVAL, "%s: softmax_scale must be positive and finite", fn);
+    const size_t need = allrows_workspace_bytes(*dims);
+    if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
+    if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
+    return launch_score_all_rows(Q, K, *dims, softmax_scale, mass, rank, ws, (hipStream_t)stream);
 }
 
 int zipvl_select(const float* mass, const float* rank, int units, int n, double tau,

@@ -316,6 +316,44 @@ def test_layer_with_hybrid_probe_set():
     _layer_parity(w, 0.975)
 
 
+# ------------------------------------------------------------------ all-rows (exact) scores
+@pytest.mark.parametrize("case", [dict(B=1, Hq=4, Hkv=2, n=333, d=128, dtype="bf16"),
+                                  dict(B=2, Hq=2, Hkv=2, n=200, d=64, dtype="f32"),
+                                  dict(B=1, Hq=14, Hkv=2, n=700, d=128, dtype="bf16"),
+                                  dict(B=1, Hq=2, Hkv=1, n=129, d=128, dtype="f32"),
+                                  dict(B=1, Hq=2, Hkv=2, n=64, d=64, dtype="bf16"),
+                                  dict(B=1, Hq=1, Hkv=1, n=1, d=128, dtype="bf16")])
+def test_all_rows_scores_match_the_oracle(case):
+    B, Hq, Hkv, n, d, dtype = (case[key] for key in ("B", "Hq", "Hkv", "n", "d", "dtype"))
+    say(f"score_all_rows B={B} Hq={Hq} Hkv={Hkv} n={n} d={d} {dtype}")
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=71, m=min(64, n))
+    Q, K = dev(w.Q, dtype), dev(w.K, dtype)
+    mass, rank = z.zipvl_score_all_rows(Q, K, w.scale)
+    mass_only, none = z.zipvl_score_all_rows(Q, K, w.scale, want_rank=False)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(mass, mass_only)
+    mass_h, rank_h = mass.cpu().numpy().astype(np.float64), rank.cpu().numpy().astype(np.float64)
+    for b in range(B):
+        mo, ro = oz.token_scores(w.Q[b], w.K[b], np.arange(n), w.scale)       # every row is a probe
+        assert_scores_close(mass_h.reshape(B, Hkv, n)[b], mo, dtype, "mass")
+        assert_scores_close(rank_h.reshape(B, Hkv, n)[b], ro, dtype, "rank")
+    assert np.all(np.abs(mass_h.sum(axis=1) - 1.0) < 1e-4)
+
+
+def test_all_rows_scores_at_cfg2_shape_against_sampled_columns():
+    say("score_all_rows at n=3072, 32 heads (sampled heads)")
+    w = make_workload(2)
+    spec = w.spec
+    Q, K = dev(w.Q, spec.dtype), dev(w.K, spec.dtype)
+    mass, rank = z.zipvl_score_all_rows(Q, K, w.scale)
+    torch.cuda.synchronize()
+    n = spec.n
+    for u in (0, 13, 31):
+        mo, ro = oz.token_scores(w.Q[0, u:u + 1], w.K[0, u:u + 1], np.arange(n), w.scale)
+        assert_scores_close(mass[u].cpu().numpy().astype(np.float64)[None], mo, spec.dtype, "mass")
+        assert_scores_close(rank[u].cpu().numpy().astype(np.float64)[None], ro, spec.dtype, "rank")
+
+
 # ------------------------------------------------------------------ one T per layer
 def test_share_scores_bit_exact():
     say("share_scores")
