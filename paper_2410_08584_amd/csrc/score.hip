@@ -45,7 +45,9 @@ __device__ __forceinline__ void load_row_frags(const T* row, int h, uintx4 (&f)[
 
 // PASS 1: partial[(bh * nsplit + split) * 64 + probe] = (raw-logit maximum, sum of exp2((s - max) * c))
 // PASS 2: mass / rank of the workgroup's keys, from bias[bh * 64 + probe] = max * c + log2(sum)
-template <typename T, int D, int PASS, int NB>
+// GCT = query heads whose probe rows are staged in LDS at once (1 when the group has a single head: fewer
+// staging registers and a smaller LDS footprint, so more workgroups per CU hide the load latency)
+template <typename T, int D, int PASS, int NB, int GCT>
 __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
     const T* __restrict__ Q, const T* __restrict__ K,
     int64_t qs0, int64_t qs1, int64_t qs2, int64_t ks0, int64_t ks1, int64_t ks2,
@@ -86,12 +88,12 @@ __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
     const bool masked = has_pad || jb + 31 > Pmin;          // wave-uniform
 
     float colsum = 0.f;                                     // PASS 2
-    float2* wstat = reinterpret_cast<float2*>(smem + C::GC * C::HEAD_BYTES);   // PASS 1: [wave][head of chunk][nb][lane]
+    float2* wstat = reinterpret_cast<float2*>(smem + GCT * C::HEAD_BYTES);   // PASS 1: [wave][head of chunk][nb][lane]
 
     // Probe rows travel global -> registers -> LDS one chunk of GC heads at a time; the next chunk
     // is requested before the current one is consumed, so its latency hides under the matrix work.
-    constexpr int NPRE = C::GC * kProbes * C::CPR / kScoreThreads;
-    static_assert(NPRE * kScoreThreads == C::GC * kProbes * C::CPR, "chunk must divide evenly over the threads");
+    constexpr int NPRE = GCT * kProbes * C::CPR / kScoreThreads;
+    static_assert(NPRE * kScoreThreads == GCT * kProbes * C::CPR, "chunk must divide evenly over the threads");
     uintx4 pre[NPRE];
     // where this thread's NPRE chunks sit inside a chunk of heads: fixed for the whole kernel
     int pre_head[NPRE];
@@ -105,13 +107,13 @@ __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
     }
     auto fetch_chunk = [&](int h0) {
         const T* base = Q + b * qs0 + (int64_t)(g * G + h0) * qs1;
-        const int last = min(C::GC, G - h0) - 1;               // heads beyond the chunk re-read its last head
+        const int last = min(GCT, G - h0) - 1;               // heads beyond the chunk re-read its last head
 #pragma unroll
         for (int q = 0; q < NPRE; ++q) pre[q] = load16(base + min(pre_head[q], last) * qs1 + pre_off[q]);
     };
     fetch_chunk(0);
-    for (int h0 = 0; h0 < G; h0 += C::GC) {
-        const int gc = min(C::GC, G - h0);
+    for (int h0 = 0; h0 < G; h0 += GCT) {
+        const int gc = min(GCT, G - h0);
         if (h0) __syncthreads();                            // previous chunk fully consumed
 #pragma unroll
         for (int q = 0; q < NPRE; ++q) {
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
             store16(smem + row * C::QS + cc * 16, pre[q]);  // rows beyond gc heads hold duplicates, never read
         }
         __syncthreads();
-        if (h0 + C::GC < G) fetch_chunk(h0 + C::GC);
+        if (h0 + GCT < G) fetch_chunk(h0 + GCT);
 #pragma unroll 1
         for (int hh = 0; hh < gc; ++hh) {
             const char* qh = smem + hh * C::HEAD_BYTES;
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
                         colsum += sum;
                     }
                 }
-                if (PASS == 1) wstat[((w * C::GC + hh) * kNB + nb) * 64 + lane] = stat;
+                if (PASS == 1) wstat[((w * GCT + hh) * kNB + nb) * 64 + lane] = stat;
             }
         }
         if (PASS == 1) {
@@ -192,14 +194,14 @@ __global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
                 for (int ww = 0; ww < kScoreWaves; ++ww)
 #pragma unroll
                     for (int hf = 0; hf < 2; ++hf)
-                        M = fmaxf(M, wstat[((ww * C::GC + hh) * kNB + nb) * 64 + hf * 32 + ii].x);
+                        M = fmaxf(M, wstat[((ww * GCT + hh) * kNB + nb) * 64 + hf * 32 + ii].x);
                 float L = 0.f;
                 if (M > -INFINITY) {
 #pragma unroll
                     for (int ww = 0; ww < kScoreWaves; ++ww)
 #pragma unroll
                         for (int hf = 0; hf < 2; ++hf) {
-                            const float2 v = wstat[((ww * C::GC + hh) * kNB + nb) * 64 + hf * 32 + ii];
+                            const float2 v = wstat[((ww * GCT + hh) * kNB + nb) * 64 + hf * 32 + ii];
                             L += v.y * fast_exp2((v.x - M) * c);
                         }
                 }
@@ -272,8 +274,8 @@ size_t score_workspace_bytes(const zipvl_dims& d, int m) {
     return score_partial_bytes(d, m) + (size_t)d.B * d.Hq * probe_rows(m) * sizeof(float);
 }
 
-template <typename T, int D, int NB>
-static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
+template <typename T, int D, int NB, int GCT>
+static int launch_score_g(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
                           int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
 {
     using C = ScoreCfg<T, D, NB>;
@@ -282,13 +284,13 @@ static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, con
     float* bias = (float*)((char*)ws + score_partial_bytes(d, m));
     const int units = d.B * d.Hkv;
     // probe rows of GC heads, then the per-wave statistics of pass 1
-    const size_t lds = (size_t)C::GC * C::HEAD_BYTES + (size_t)kScoreWaves * C::GC * NB * 64 * sizeof(float2);
+    const size_t lds = (size_t)GCT * C::HEAD_BYTES + (size_t)kScoreWaves * GCT * NB * 64 * sizeof(float2);
     static bool attr_done = false;
     if (!attr_done) {
         const int cap = 96 * 1024;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 1, NB>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 1, NB, GCT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 2, NB>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 2, NB, GCT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
             return set_error(ZIPVL_EHIP, "score: cannot reserve LDS for the probe rows");
         attr_done = true;
@@ -296,7 +298,7 @@ static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, con
     const int nsplit = (n_eff + kScoreKeys - 1) / kScoreKeys;
     {
         KernelTimer tm(ZIPVL_K_SCORE_ROWSTATS, st);
-        hipLaunchKernelGGL((score_pass_kernel<T, D, 1, NB>), dim3(nsplit, units), dim3(kScoreThreads), lds, st,
+        hipLaunchKernelGGL((score_pass_kernel<T, D, 1, NB, GCT>), dim3(nsplit, units), dim3(kScoreThreads), lds, st,
             (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, partial, nsplit,
             (const float*)nullptr, (float*)nullptr, (float*)nullptr, d.Hq, d.Hkv);
@@ -311,11 +313,22 @@ static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, con
     rc = check_launch("score_rowfinal");
     if (rc) return rc;
     KernelTimer tm(ZIPVL_K_SCORE_COLSUM, st);
-    hipLaunchKernelGGL((score_pass_kernel<T, D, 2, NB>), dim3(score_splits(d), units), dim3(kScoreThreads), lds, st,
+    hipLaunchKernelGGL((score_pass_kernel<T, D, 2, NB, GCT>), dim3(score_splits(d), units), dim3(kScoreThreads), lds, st,
         (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
         d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, (float2*)nullptr, nsplit,
         (const float*)bias, mass, rank, d.Hq, d.Hkv);
     return check_launch("score_colsum");
+}
+
+template <typename T, int D, int NB>
+static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
+                          int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
+{
+    constexpr int GC = ScoreCfg<T, D, NB>::GC;
+    if constexpr (GC > 1) {
+        if (d.Hq == d.Hkv) return launch_score_g<T, D, NB, 1>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    }
+    return launch_score_g<T, D, NB, GC>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
 }
 
 template <typename T, int D>
