@@ -102,6 +102,11 @@ def test_select_exact_on_synthetic_distributions():
         rk = (skew * (1 + 0.5 * r.random((3, n)))).astype(np.float32)
         _select_case(f"skew-n{n}", skew, rk, 0.975)
         _select_case(f"skew-single-n{n}", skew, None, 0.9)
+    # beyond the LDS-resident key count (27648): keys are re-read from memory on every digit pass
+    for n in (27648, 27649, 131072):
+        big = norm(r.random((2, n)) ** 6 + 1e-9)
+        _select_case(f"long-n{n}", big, (big * (1 + r.random((2, n)))).astype(np.float32), 0.975)
+        _select_case(f"long-single-n{n}", big, None, 0.95)
     n = 3000
     ties = norm(np.round(r.random((2, n)) * 6) + 1.0)            # 7 distinct values: many ties
     _select_case("ties", ties, ties[:, ::-1].copy(), 0.7)
@@ -607,6 +612,12 @@ def test_layer_cfg4_headline_shape_sampled():
     say("layer cfg4 (bf16 GQA 28/4, n=18432), sampled output rows")
     w = make_workload(4)
     _layer_parity(w, w.tau, sample_rows=12, heads=[0, 6, 27])
+
+
+def test_layer_beyond_the_benchmark_lengths_sampled():
+    say("layer at n=40960 (bf16 GQA 2/1): selection keys no longer fit LDS, 320 query tiles per head")
+    w = make_custom(1, 2, 1, 40960, 128, "bf16", seed=81, spike_frac=0.05)
+    _layer_parity(w, 0.975, sample_rows=10)
 
 
 def test_layer_cfg5_first_and_last_layer_then_decode_on_evicted_cache():
