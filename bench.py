@@ -414,7 +414,8 @@ def main():
     hbm["select"] = float(units * (8 * n) + 4 * k_h.sum() + 4 * units) / (kern["select"]["avg_us"] * 1e-6) / 1e9
     kv_bytes = float(sum(2 * 2 * kk * d * e + 4 * kk for kk in k_h))
     hbm["compact_kv"] = kv_bytes / (kern["compact_kv"]["avg_us"] * 1e-6) / 1e9
-    hbm["pack_kv"] = kv_bytes / (kern["pack_kv"]["avg_us"] * 1e-6) / 1e9
+    if "pack_kv" in kern:                                    # not launched when the evicted cache is read in place
+        hbm["pack_kv"] = kv_bytes / (kern["pack_kv"]["avg_us"] * 1e-6) / 1e9
 
     out = {
         "metric": "sparse-prefill dense-equivalent TFLOP/s (ms/layer in ms_per_step, tokens kept % in kept_pct)",

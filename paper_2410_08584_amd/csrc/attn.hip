@@ -2,10 +2,11 @@
 // step; Eq. (2) restricted to the important set T).
 //
 // Two kernels:
-//   pack   gathers K[T] row-major and V[T] transposed ([d][64 keys] tiles) into
-//          the workspace, once per KV head, zero-filling the ragged tail.  The
-//          transposed V is what lets the P.V product read both MFMA operands
-//          as contiguous fragments (the contraction runs over keys).
+//   pack   gathers K[T] and V[T] into the workspace, once per KV head, zero-filling
+//          the ragged tail.  bf16: both row-major (the P.V operand is fetched from
+//          LDS with the transposing read, so an evicted cache with whole tiles is
+//          read in place and nothing is packed at all); fp32: V[T] transposed
+//          ([d][64 keys] tiles), so that both MFMA operands are contiguous fragments.
 //   flash  one workgroup = 128 kept queries of one query head (4 waves x 32
 //          rows).  K / V^T tiles of 64 keys are loaded straight into LDS
 //          (double buffered, one barrier per tile) and shared by the four waves;
@@ -52,37 +53,34 @@ struct AttnCfg {
     // LDS tiles are unpadded; the 16-byte chunks of a row are XOR-swizzled with (row & 7) instead, so
     // that any 8 consecutive rows read at the same logical chunk hit 8 different bank groups.
     static constexpr int KRB = D * E;                        // bytes per K row
-    static constexpr int VRB = kBN * E;                      // bytes per V^T row
-    static constexpr int TILE_BYTES = kBN * D * E;           // one K tile = one V^T tile
+    // bf16: V tiles stay row-major ([64 keys][d], like K) and the P.V operand is fetched with the LDS
+    // transposing read; fp32 (no such read for 32-bit elements): V^T tiles ([d][64 keys]) packed beforehand.
+    static constexpr bool VROWS = E == 2;
+    static constexpr int VRB = VROWS ? D * E : kBN * E;      // bytes per row of a V tile
+    static constexpr int TILE_BYTES = kBN * D * E;           // one K tile = one V tile
     static constexpr int NLD = TILE_BYTES / 1024 / NW;       // 1-KiB direct-to-LDS loads per wave per tile
-    static constexpr int LDS_BYTES = 4 * TILE_BYTES;         // two K and two V^T buffers
+    static constexpr int LDS_BYTES = 4 * TILE_BYTES;         // two K and two V buffers
     // bf16, QB = 1: two waves per SIMD (<= 256 registers, accumulators stay in VGPRs); otherwise one
     // wave per SIMD with the whole 512-entry register file
     static constexpr int MIN_WGS = (E == 2 && QB == 1) ? 8 / NW : 1;
 };
 
 // ------------------------------------------------------------------ pack
-// Key held at element e of 16-byte chunk kc of a V^T tile row.  fp32: natural order.  bf16: inside
-// every group of 16 keys the order is [0..3, 8..11 | 4..7, 12..15], which is the order in which the
-// two half-waves hold the 8 contraction slots of one P^T fragment, so that a lane's V^T operand is
-// one contiguous 16-byte read.
-template <typename T> __device__ __forceinline__ int vt_key(int kc, int e);
-template <> __device__ __forceinline__ int vt_key<float>(int kc, int e) { return kc * 4 + e; }
-template <> __device__ __forceinline__ int vt_key<__bf16>(int kc, int e) {
-    return 16 * (kc >> 1) + 8 * (e >> 2) + 4 * (kc & 1) + (e & 3);
-}
+// Key held at element e of 16-byte chunk kc of a V^T tile row (fp32 path): natural order.
+__device__ __forceinline__ int vt_key(int kc, int e) { return kc * 4 + e; }
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void pack_kv_kernel(
     const T* __restrict__ K, const T* __restrict__ V,
     int64_t ks0, int64_t ks1, int64_t ks2, int64_t vs0, int64_t vs1, int64_t vs2,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
-    T* __restrict__ Kp, T* __restrict__ VTp, int n, int npad, int Hkv, int rows_are_kept, int skip_k, int t_per_batch)
+    T* __restrict__ Kp, T* __restrict__ Vp, int n, int npad, int Hkv, int rows_are_kept, int skip_k, int t_per_batch)
 {
     constexpr int EPF = Elem<T>::kPerFrag;
     constexpr int CPR = D / EPF;
     constexpr int LS = D + EPF;                 // padded LDS row (elements)
-    __shared__ __attribute__((aligned(16))) T tile[kBN * LS];
+    constexpr bool VROWS = Elem<T>::kBytes == 2;
+    __shared__ __attribute__((aligned(16))) T tile[VROWS ? EPF : kBN * LS];
     const int u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
     const int t0 = blockIdx.x * kBN;
     const int ut = t_per_batch ? b : u;                   // row of idx / k that holds this unit's T
@@ -100,15 +98,17 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
             vv = load16(Vb + (int64_t)src * vs2 + cc * EPF);
         }
         if (!skip_k) store16(Kp + ((int64_t)u * npad + row) * D + cc * EPF, kv);
-        store16(tile + r * LS + cc * EPF, vv);
+        if (VROWS) store16(Vp + ((int64_t)u * npad + row) * D + cc * EPF, vv);      // rows past k are zero rows
+        else store16(tile + r * LS + cc * EPF, vv);
     }
+    if (VROWS) return;
     __syncthreads();
-    T* VT = VTp + ((int64_t)u * (npad / kBN) + blockIdx.x) * (D * kBN);
+    T* VT = Vp + ((int64_t)u * (npad / kBN) + blockIdx.x) * (D * kBN);
     for (int wi = threadIdx.x; wi < D * (kBN / EPF); wi += 256) {
         const int dd = wi % D, kc = wi / D;
         T v[EPF];
 #pragma unroll
-        for (int e = 0; e < EPF; ++e) v[e] = tile[vt_key<T>(kc, e) * LS + dd];
+        for (int e = 0; e < EPF; ++e) v[e] = tile[vt_key(kc, e) * LS + dd];
         store16(VT + dd * kBN + kc * EPF, *reinterpret_cast<const uintx4*>(v));
     }
 }
@@ -155,13 +155,19 @@ __device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w
 }
 
 // per-lane source offsets for tile_to_lds (rows of RB bytes)
-template <int RB, int NW, int NLD>
+// Row swizzle of a row-major bf16 V tile (rows of RB bytes): the transposing read of a 16-lane group
+// touches 4 consecutive keys x 4 consecutive 16-byte chunks, so the key index goes into chunk bits 2..3
+// (one bit of it is already an address bit when two rows share a 256-byte bank period).
+template <int RB>
+__device__ __forceinline__ int v_row_swizzle(int row) { return ((row & 3) >> (RB == 128 ? 1 : 0)) << 2; }
+
+template <int RB, int NW, int NLD, bool VSWZ = false>
 __device__ __forceinline__ void lds_fill_offsets(int w, int lane, int (&off)[NLD]) {
 #pragma unroll
     for (int q = 0; q < NLD; ++q) {
         const int o = (q * NW + w) * 1024 + lane * 16;
         const int r = o / RB, p = (o % RB) >> 4;
-        off[q] = r * RB + ((p ^ (r & 7)) << 4);
+        off[q] = r * RB + ((p ^ (VSWZ ? v_row_swizzle<RB>(r) : (r & 7))) << 4);
     }
 }
 
@@ -190,17 +196,33 @@ template <typename T, int D, int NW, int QB> struct PV;
 template <int D, int NW, int QB> struct PV<__bf16, D, NW, QB> {
     using C = AttnCfg<__bf16, D, NW, QB>;
     // p[qb][blk][s2]: the probabilities of S^T block blk as P^T operand fragments.  Contraction slot t of
-    // this lane <-> key 16*s2 + 8*(t/4) + 4*h + t%4 of the block = accumulator register 8*s2 + t; V^T rows
-    // are stored in slot order, so the matching V^T operand is one 16-byte chunk.
+    // this lane <-> key 16*s2 + 8*(t/4) + 4*h + t%4 of the block = accumulator register 8*s2 + t.
     using Probs = uintx4[QB][2][2];
+    // The matching V^T operand (lane = channel 32 db + lane % 32, slots = those 8 keys) comes from the
+    // row-major V tile through ds_read_b64_tr_b16: in every group of 16 lanes, lane 4e + q supplies the
+    // address of 4 consecutive channels of key e, and lane l receives channel l of keys 0..3.  Two reads
+    // (keys +0..3 and +8..11 relative to 16 s2 + 4 h) make one operand.  lane_off[db]: this lane's
+    // supplier address inside a tile for channel block db (row swizzle included).
+    __device__ static __forceinline__ void lane_offsets(int lane, int (&lane_off)[C::ODB]) {
+        const int h = lane >> 5, grp = (lane >> 4) & 1, e = (lane >> 2) & 3, q = lane & 3;
+        const int row = 4 * h + e;                           // key inside its group of 8 = swizzle of the row
+#pragma unroll
+        for (int db = 0; db < C::ODB; ++db)
+            lane_off[db] = row * C::VRB + swz_chunk(4 * db + 2 * grp + (q >> 1), v_row_swizzle<C::VRB>(row)) + (q & 1) * 8;
+    }
     template <int HALF>
-    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const Probs& p, floatx16 (&o)[QB][C::ODB]) {
+    __device__ static __forceinline__ void run(const char* vb, const int (&lane_off)[C::ODB], const Probs& p,
+                                               floatx16 (&o)[QB][C::ODB]) {
+        typedef short shortx4 __attribute__((ext_vector_type(4)));
+        using lds_ptr = __attribute__((address_space(3))) shortx4*;
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-            const int chunk = swz_chunk(2 * (2 * HALF + s2) + h, sw);
 #pragma unroll
             for (int db = 0; db < C::ODB; ++db) {
-                const uintx4 vf = *reinterpret_cast<const uintx4*>(vb + (db * 32 + i) * C::VRB + chunk);
+                const char* a0 = vb + lane_off[db] + (32 * HALF + 16 * s2) * C::VRB;
+                const uintx2 lo = __builtin_bit_cast(uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)a0));
+                const uintx2 hi = __builtin_bit_cast(uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0 + 8 * C::VRB)));
+                const uintx4 vf = {lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) o[qb][db] = mma_frag<__bf16>(vf, p[qb][HALF][s2], o[qb][db]);
             }
@@ -211,8 +233,14 @@ template <int D, int NW, int QB> struct PV<__bf16, D, NW, QB> {
 template <int D, int NW, int QB> struct PV<float, D, NW, QB> {
     using C = AttnCfg<float, D, NW, QB>;
     using Probs = floatx16[QB][2];                           // p[qb][blk][r]: as the S^T accumulators
+    // lane_off[0] = V^T row of this lane inside a channel block and [1] = its swizzle (i, i & 7)
+    __device__ static __forceinline__ void lane_offsets(int lane, int (&lane_off)[C::ODB]) {
+        lane_off[0] = lane & 31;
+        lane_off[1] = lane >> 5;
+    }
     template <int HALF>
-    __device__ static __forceinline__ void run(const char* vb, int i, int h, int sw, const Probs& p, floatx16 (&o)[QB][C::ODB]) {
+    __device__ static __forceinline__ void run(const char* vb, const int (&lane_off)[C::ODB], const Probs& p, floatx16 (&o)[QB][C::ODB]) {
+        const int i = lane_off[0], h = lane_off[1], sw = i & 7;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             // step (a, t): this lane contributes key 32*HALF + 8*a + 4*h + t
@@ -240,9 +268,15 @@ __device__ __forceinline__ void flash_schedule() {
 #pragma unroll
         for (int q = 0; q < kSchedAhead; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
 #pragma unroll
-        for (int q = 0; q < 32; ++q) {
+        for (int q = 0; q < 13; ++q) {
             __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                       // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                        // LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, kSchedValu * QB, 0);          // vector ALU
+        }
+#pragma unroll
+        for (int q = 13; q < 32; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                       // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                        // LDS reads: two per P.V operand
             __builtin_amdgcn_sched_group_barrier(0x002, kSchedValu * QB, 0);          // vector ALU
         }
     }
@@ -282,10 +316,10 @@ template <> __device__ __forceinline__ void store_out4<__bf16>(__bf16* dst, floa
 template <typename T, int D, int NW, int QB>
 __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void flash_kept_kernel(
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
-    const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ VTp,
+    const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ Vp, int64_t vp0, int64_t vp1,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
     T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped,
-    int t_per_batch)
+    int t_per_batch, int v_in_place)
 {
     using C = AttnCfg<T, D, NW, QB>;
     constexpr int kBM = C::BM, kNT = C::NT, kRW = 32 * QB;   // queries per workgroup, threads, queries per wave
@@ -362,13 +396,15 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     const int wave_first_row = i0 + kRW * w, wave_last_row = wave_first_row + kRW - 1;
     const int my_tiles = min(ntiles, wave_last_row / kBN + 1);   // later tiles lie wholly in this wave's future
     const char* kg = reinterpret_cast<const char*>(Kp + b * kp0 + g * kp1);   // row-major kept K rows of this unit
-    const char* vg = reinterpret_cast<const char*>(VTp + (int64_t)u * npad * D);
+    const char* vg = reinterpret_cast<const char*>(Vp + b * vp0 + g * vp1);   // V tiles of this unit (V^T tiles for fp32)
     char* const Kb0 = smem;
     char* const Vb0 = smem + 2 * C::TILE_BYTES;
     const int sw = i & 7;
     int koff[C::NLD], voff[C::NLD];
     lds_fill_offsets<C::KRB, NW, C::NLD>(w, lane, koff);
-    lds_fill_offsets<C::VRB, NW, C::NLD>(w, lane, voff);
+    lds_fill_offsets<C::VRB, NW, C::NLD, C::VROWS>(w, lane, voff);
+    int vlane[C::ODB];
+    PV<T, D, NW, QB>::lane_offsets(lane, vlane);
 
     // Software pipeline over key tiles.  While tile t is in its softmax (vector ALU) and P.V (matrix)
     // stages, the S^T product of tile t+1 already runs on the matrix cores and the loads of K tile t+2
@@ -411,6 +447,14 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
                     pinned = __uint_as_float(pin);
                 }
         };
+        if (C::VROWS && v_in_place && (t + 1) * kBN > kk) {
+            // A V tile read in place from the evicted cache may hold anything in its rows past k; their
+            // probabilities are exact zeros, but 0 * NaN is not: clear those rows in LDS (last tile only).
+            char* vt = Vb0 + (t & 1) * C::TILE_BYTES;
+            const uintx4 z = {0, 0, 0, 0};
+            for (int q = tid + (kk - t * kBN) * (C::VRB / 16); q < kBN * (C::VRB / 16); q += kNT) store16(vt + q * 16, z);
+            __syncthreads();
+        }
         if (t < my_tiles) {
             const int t0 = t * kBN;
             const char* kb = Kb0 + ((t + 1) & 1) * C::TILE_BYTES;
@@ -493,16 +537,16 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
                 qk_block<T, D, NW, QB>(kb, 0, i, h, sw, qf, sn);
                 qk_block<T, D, NW, QB>(kb, 1, i, h, sw, qf, sn);
                 exps(0, true);
-                PV<T, D, NW, QB>::template run<0>(vb, i, h, sw, pr, o);
+                PV<T, D, NW, QB>::template run<0>(vb, vlane, pr, o);
                 exps(1, true);
-                PV<T, D, NW, QB>::template run<1>(vb, i, h, sw, pr, o);
+                PV<T, D, NW, QB>::template run<1>(vb, vlane, pr, o);
                 flash_schedule<T, D, QB>();
             } else {
                 fetch_all();
                 exps(0, false);
-                PV<T, D, NW, QB>::template run<0>(vb, i, h, sw, pr, o);
+                PV<T, D, NW, QB>::template run<0>(vb, vlane, pr, o);
                 exps(1, false);
-                PV<T, D, NW, QB>::template run<1>(vb, i, h, sw, pr, o);
+                PV<T, D, NW, QB>::template run<1>(vb, vlane, pr, o);
             }
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
@@ -543,7 +587,7 @@ size_t prefill_workspace_bytes(const zipvl_dims& d) {
 
 template <typename T, int D, int NW, int QB>
 static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const int32_t* idx, const int32_t* k,
-                        float scale, int out_compact, int t_per_batch, int skip_k, const T* Kp, const T* VTp, int npad, void* O, hipStream_t st)
+                        float scale, int out_compact, int t_per_batch, int skip_k, int skip_v, const void* V, const T* Kp, const T* Vp, int npad, void* O, hipStream_t st)
 {
     using C = AttnCfg<T, D, NW, QB>;
     static bool attr_done = false;       // raising the dynamic-LDS cap is idempotent
@@ -565,8 +609,10 @@ static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const
         hipLaunchKernelGGL((flash_kept_kernel<T, D, NW, QB>), dim3((unsigned)blocks), dim3(C::NT),
             C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             skip_k ? (const T*)K : Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
-            skip_k ? d.k_strides[1] : (int64_t)npad * D, VTp, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
-            scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0, t_per_batch);
+            skip_k ? d.k_strides[1] : (int64_t)npad * D,
+            skip_v ? (const T*)V : Vp, skip_v ? d.v_strides[0] : (int64_t)d.Hkv * npad * D,
+            skip_v ? d.v_strides[1] : (int64_t)npad * D, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
+            scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0, t_per_batch, skip_v);
     }
     return check_launch("flash_kept");
 }
@@ -584,24 +630,25 @@ static int launch_prefill_t(const void* Q, const void* K, const void* V, const z
     const int rows_are_kept = (flags & ZIPVL_KV_ALREADY_COMPACT) ? 1 : 0;
     const int t_per_batch = (flags & ZIPVL_T_PER_BATCH) ? 1 : 0;
 
-    // An evicted cache with contiguous rows and whole 64-row tiles is read in place: only V is repacked.
-    // (Rows between k and the end of the last tile may hold anything: they are masked, never summed.)
-    const int skip_k = (rows_are_kept && d.k_strides[2] == D && d.n % kBN == 0) ? 1 : 0;
-    {
+    // An evicted cache with contiguous rows and whole 64-row tiles is read in place (K always, V when the
+    // transposing LDS read applies: then nothing is packed).  Rows between k and the end of the last tile
+    // may hold anything: K rows there are masked, V rows there are cleared once they are in LDS.
+    const int in_place = (rows_are_kept && d.n % kBN == 0) ? 1 : 0;
+    const int skip_k = (in_place && d.k_strides[2] == D) ? 1 : 0;
+    const int skip_v = (in_place && Elem<T>::kBytes == 2 && d.v_strides[2] == D) ? 1 : 0;
+    if (!(skip_k && skip_v)) {
         KernelTimer tm(ZIPVL_K_PACK_KV, st);
         hipLaunchKernelGGL((pack_kv_kernel<T, D>), dim3(npad / kBN, units), dim3(256), 0, st,
             (const T*)K, (const T*)V, d.k_strides[0], d.k_strides[1], d.k_strides[2],
             d.v_strides[0], d.v_strides[1], d.v_strides[2], idx, k, Kp, VTp, d.n, npad, d.Hkv, rows_are_kept, skip_k, t_per_batch);
+        int rc = check_launch("pack_kv");
+        if (rc) return rc;
     }
-    int rc = check_launch("pack_kv");
-    if (rc) return rc;
 
-    // bf16: 8 waves share every tile (half the L2 -> LDS traffic per query); fp32 keeps 4 waves
-    // (its tiles are twice as large and it runs one wave per SIMD).
     if constexpr (Elem<T>::kBytes == 2)
-        return launch_flash<T, D, kFlashWavesBf16, kFlashBlocksBf16>(Q, K, d, idx, k, scale, out_compact, t_per_batch, skip_k, Kp, VTp, npad, O, st);
+        return launch_flash<T, D, kFlashWavesBf16, kFlashBlocksBf16>(Q, K, d, idx, k, scale, out_compact, t_per_batch, skip_k, skip_v, V, Kp, VTp, npad, O, st);
     else
-        return launch_flash<T, D, 4, 1>(Q, K, d, idx, k, scale, out_compact, t_per_batch, skip_k, Kp, VTp, npad, O, st);
+        return launch_flash<T, D, 4, 1>(Q, K, d, idx, k, scale, out_compact, t_per_batch, skip_k, skip_v, V, Kp, VTp, npad, O, st);
 }
 
 int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims& d,
