@@ -13,6 +13,8 @@
 // (streamed rows) x (register rows)^T on 32x32 tiles, so a lane owns one register-side
 // row and its statistic (running max / sum in pass 1, column sum in pass 2) never
 // leaves the lane until the end.
+#include <atomic>
+
 #include "launch.h"
 
 namespace zipvl {
@@ -183,7 +185,7 @@ static int launch_allrows_t(const void* Q, const void* K, const zipvl_dims& d, f
 {
     using C = ArCfg<T, D>;
     const size_t lds = 2 * (size_t)C::BUF + 2 * kArChunk * sizeof(float);
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&allrows_pass_kernel<T, D, 1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||

@@ -26,6 +26,8 @@
 // The kept count k lives on the device: the grid covers the worst case (k = n)
 // and workgroups beyond a unit's k exit at once; heavy (late) query tiles are
 // scheduled first.
+#include <atomic>
+
 #include "launch.h"
 
 namespace zipvl {
@@ -120,6 +122,9 @@ __device__ __forceinline__ int swz_chunk(int c, int sw) { return (c ^ sw) << 4; 
 // One tile (TILE_BYTES contiguous in global memory) -> one LDS buffer, without passing through
 // registers: every wave issues NLD loads of 1 KiB, lane L of a load writes LDS bytes [16 L, 16 L + 16)
 // of that KiB, and picks the global chunk that belongs there under the row swizzle.
+// (M0 is named as clobbered on purpose: the instruction reads its LDS base from it and nothing else here uses M0.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 // One 1-KiB direct-to-LDS load of the wave: lane L's 16 bytes at gbase + goff land at LDS byte
 // lds_base + 16 L (gbase and lds_base wave-uniform, goff a per-lane byte offset below 4 GiB).
 // global_load_lds_dwordx4 takes the LDS base from M0.  The instruction is written out rather than
@@ -142,6 +147,8 @@ __device__ __forceinline__ void load_kib_to_lds_pinned(const char* gbase, int go
     asm("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
         : "+v"(pin) : "s"(m0v), "v"(goff), "s"(gbase) : "m0");
 }
+
+#pragma clang diagnostic pop
 
 __device__ __forceinline__ unsigned lds_address(const char* p) {
     return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
@@ -590,7 +597,7 @@ static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const
                         float scale, int out_compact, int t_per_batch, int skip_k, int skip_v, const void* V, const T* Kp, const T* Vp, int npad, void* O, hipStream_t st)
 {
     using C = AttnCfg<T, D, NW, QB>;
-    static bool attr_done = false;       // raising the dynamic-LDS cap is idempotent
+    static std::atomic<bool> attr_done{false};       // raising the dynamic-LDS cap is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kept_kernel<T, D, NW, QB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)

@@ -9,6 +9,8 @@
 // (rank among the others, Eq. (10)), with an LDS bitmap and a prefix count;
 // `quantize_rows` then handles 16 rows per wave pass, 16 lanes per row like the
 // decode kernels, so every code row is written as one contiguous store per lane.
+#include <atomic>
+
 #include "launch.h"
 #include "rowops.h"
 
@@ -149,7 +151,7 @@ static int launch_quantize_t(const void* K, const void* V, const zipvl_dims& d, 
     const int t_per_batch = (flags & ZIPVL_T_PER_BATCH) ? 1 : 0;
     int32_t* slot = (int32_t*)ws;
     const size_t lds = 2 * (size_t)((d.n + 31) / 32) * sizeof(uint32_t);
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&token_slots_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess)

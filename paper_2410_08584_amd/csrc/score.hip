@@ -14,6 +14,8 @@
 // accumulator.  Pass 1 computes K Q^T (lane = probe column: row statistics
 // stay in the lane); pass 2 computes Q K^T (lane = key column: column sums
 // stay in the lane).  Same fragments, operands swapped.
+#include <atomic>
+
 #include "launch.h"
 
 namespace zipvl {
@@ -285,7 +287,7 @@ static int launch_score_g(const void* Q, const void* K, const zipvl_dims& d, con
     const int units = d.B * d.Hkv;
     // probe rows of GC heads, then the per-wave statistics of pass 1
     const size_t lds = (size_t)GCT * C::HEAD_BYTES + (size_t)kScoreWaves * GCT * NB * 64 * sizeof(float2);
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         const int cap = 96 * 1024;
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 1, NB, GCT>),

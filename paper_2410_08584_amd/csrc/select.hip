@@ -17,6 +17,8 @@
 // One 1024-thread workgroup per selection unit.  Up to n = 26624 the order-preserving keys of
 // the vector in use are held in LDS (read from memory once, coalesced); longer vectors are
 // re-read per digit.
+#include <atomic>
+
 #include "launch.h"
 
 namespace zipvl {
@@ -284,7 +286,7 @@ int launch_select(const float* mass, const float* rank, int units, int n, double
 {
     const int in_lds = n <= kSelMaxLdsKeys ? 1 : 0;
     const size_t dyn = in_lds ? (size_t)n * sizeof(uint32_t) : 0;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
