@@ -259,9 +259,21 @@ int zipvl_decode_attn_q(const void* q, const zipvl_qtensor* Kq, const zipvl_qten
 #define ZIPVL_K_DECODE_Q_PARTIAL 14
 #define ZIPVL_K_ALLROWS_LSE    15
 #define ZIPVL_K_ALLROWS_COLSUM 16
-#define ZIPVL_K_COUNT          17
+#define ZIPVL_K_PROBE_MFMA     17
+#define ZIPVL_K_PROBE_READ     18
+#define ZIPVL_K_COUNT          19
 int zipvl_timing_enable(int on);
 int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
+
+/*
+ * What the GPU sustains (measurement aids for the benchmark's roofline, not part of the method).
+ * zipvl_probe_mfma: `workgroups` x 4 waves each issue iters x 8 independent 32x32x16 bf16 MFMAs
+ * (32768 flop each) and nothing else; out [device]: workgroups * 256 floats (a checksum that keeps the
+ * work alive).  zipvl_probe_stream_read: reads `bytes` (multiple of 16) of src once with 16-byte loads;
+ * out [device]: workgroups * 256 uint32.  Time them with zipvl_timing_enable / zipvl_timing_read.
+ */
+int zipvl_probe_mfma(int iters, int workgroups, float* out, void* stream);
+int zipvl_probe_stream_read(const void* src, size_t bytes, int workgroups, uint32_t* out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q, 
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
            "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
-           "zipvl_timing_enable", "zipvl_timing_read")
+           "zipvl_timing_enable", "zipvl_timing_read", "zipvl_probe_mfma", "zipvl_probe_stream_read")
 
 
 class ZipvlError(RuntimeError):
@@ -69,6 +69,10 @@ def load_library():
     lib.zipvl_decode_attn_q.argtypes = [vp, C.POINTER(QTensor), C.POINTER(QTensor), i32p, i32p, C.c_int32, C.c_int32,
                                         vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp, C.c_size_t, vp]
     lib.zipvl_score_all_rows.argtypes = [vp, vp, C.POINTER(Dims), C.c_float, f32p, f32p, vp, C.c_size_t, vp]
+    lib.zipvl_probe_mfma.argtypes = [C.c_int, C.c_int, f32p, vp]
+    lib.zipvl_probe_stream_read.argtypes = [vp, C.c_size_t, C.c_int, vp, vp]
+    lib.zipvl_probe_mfma.restype = C.c_int
+    lib.zipvl_probe_stream_read.restype = C.c_int
     lib.zipvl_share_scores.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_int, f32p, f32p, vp]
     lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
     lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
@@ -336,7 +340,32 @@ def zipvl_decode_attn_q(q: torch.Tensor, cache: QCache, softmax_scale: float, *,
 
 KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
            "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal", "share_scores",
-           "token_slots", "quantize_rows", "decode_q_partial", "allrows_lse", "allrows_colsum")
+           "token_slots", "quantize_rows", "decode_q_partial", "allrows_lse", "allrows_colsum", "probe_mfma", "probe_read")
+
+
+def zipvl_probe_peaks(device="cuda:0", iters: int = 4096, read_mib: int = 4096):
+    """(sustained bf16 MFMA TFLOP/s, sustained read GB/s) of this GPU, from the library's two probe kernels."""
+    lib = load_library()
+    wgs = 2048                                               # 8 workgroups per CU queue up; 2 are resident (256 CUs)
+    out = torch.empty((wgs * 256,), dtype=torch.float32, device=device)
+    src = torch.empty((read_mib << 20,), dtype=torch.uint8, device=device).fill_(3)
+    outr = torch.empty((4096 * 256,), dtype=torch.int32, device=device)
+    res = []
+    for kid, call in ((KERNELS.index("probe_mfma"), lambda: lib.zipvl_probe_mfma(iters, wgs, _ptr(out), _stream())),
+                      (KERNELS.index("probe_read"), lambda: lib.zipvl_probe_stream_read(_ptr(src), src.numel(), 4096, _ptr(outr), _stream()))):
+        for _ in range(3):
+            _check(call())
+        torch.cuda.synchronize()
+        zipvl_timing_enable(True)
+        for _ in range(5):
+            _check(call())
+        torch.cuda.synchronize()
+        ms, cnt = zipvl_timing_read(kid)
+        zipvl_timing_enable(False)
+        res.append(ms / cnt)
+    tflops = wgs * 4 * iters * 8 * 32768.0 / (res[0] * 1e-3) / 1e12
+    gbps = src.numel() / (res[1] * 1e-3) / 1e9
+    return tflops, gbps
 
 
 def zipvl_timing_enable(on: bool) -> None:

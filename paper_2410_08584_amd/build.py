@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzipvl.so")
-SOURCES = ["zipvl_api.hip", "score.hip", "select.hip", "attn.hip", "compact.hip", "decode.hip", "quant.hip", "allrows.hip"]
+SOURCES = ["zipvl_api.hip", "score.hip", "select.hip", "attn.hip", "compact.hip", "decode.hip", "quant.hip", "allrows.hip", "peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]

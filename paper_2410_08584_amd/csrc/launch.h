@@ -51,4 +51,7 @@ int launch_decode_attn_q(const void* q, const zipvl_qtensor& Kq, const zipvl_qte
                          const int32_t* len_lo, int32_t cap_hi, int32_t cap_lo, const void* Kt, const void* Vt,
                          const int32_t* len_t, int32_t cap_t, const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);
 
+int launch_probe_mfma(int iters, int workgroups, float* out, hipStream_t st);
+int launch_probe_read(const void* src, size_t bytes, int workgroups, uint32_t* out, hipStream_t st);
+
 }  // namespace zipvl

@@ -317,6 +317,19 @@ int zipvl_decode_attn_q(const void* q, const zipvl_qtensor* Kq, const zipvl_qten
                                 *dims, softmax_scale, o, ws, (hipStream_t)stream);
 }
 
+int zipvl_probe_mfma(int iters, int workgroups, float* out, void* stream)
+{
+    if (iters < 1 || workgroups < 1 || !out) return set_error(ZIPVL_EINVAL, "zipvl_probe_mfma: iters, workgroups must be positive and out given");
+    return launch_probe_mfma(iters, workgroups, out, (hipStream_t)stream);
+}
+
+int zipvl_probe_stream_read(const void* src, size_t bytes, int workgroups, uint32_t* out, void* stream)
+{
+    if (!src || !out || workgroups < 1 || bytes < 16 || (bytes & 15)) return set_error(ZIPVL_EINVAL, "zipvl_probe_stream_read: src, out, workgroups >= 1 and bytes a positive multiple of 16 are required");
+    if (!aligned16(src)) return set_error(ZIPVL_EALIGN, "zipvl_probe_stream_read: src is not 16-byte aligned");
+    return launch_probe_read(src, bytes, workgroups, out, (hipStream_t)stream);
+}
+
 int zipvl_timing_enable(int on) {
     std::lock_guard<std::mutex> lk(g_tmu);
     g_timed.clear();
