@@ -26,6 +26,7 @@
 // The kept count k lives on the device: the grid covers the worst case (k = n)
 // and workgroups beyond a unit's k exit at once; heavy (late) query tiles are
 // scheduled first.
+#include <algorithm>
 #include <atomic>
 
 #include "launch.h"
@@ -38,6 +39,7 @@ constexpr int kBN = 64;      // keys per tile
 // not fit the register file with the S^T double buffer and spills.
 constexpr int kFlashWavesBf16 = 4;
 constexpr int kFlashBlocksBf16 = 1;
+constexpr int kFillSpan = 512;       // positions per workgroup that clears dropped output rows
 constexpr float kLazyLog2 = 8.f;     // slack of the running softmax offset below the running maximum (log2 domain)
 constexpr int kSchedAhead = 3;       // LDS operand reads in flight ahead of the consuming MFMA
 constexpr int kSchedValu = 4;        // vector instructions placed between two MFMAs
@@ -289,16 +291,6 @@ __device__ __forceinline__ void flash_schedule() {
     }
 }
 
-// rows [lo, hi) of head bh of O := 0, spread over `nthreads` threads (16-byte stores)
-template <typename T, int D>
-__device__ __forceinline__ void zero_rows(T* O, int bh, int n, int lo, int hi, int tid, int nthreads) {
-    constexpr int CPR = D * Elem<T>::kBytes / 16;
-    const uintx4 z = {0, 0, 0, 0};
-    char* base = reinterpret_cast<char*>(O + ((int64_t)bh * n + lo) * D);
-    const int64_t chunks = (int64_t)(hi - lo) * CPR;
-    for (int64_t q = tid; q < chunks; q += nthreads) store16(base + q * 16, z);
-}
-
 // The two half-waves (lanes l and l ^ 32) hold the two halves of each query's keys: combine a per-lane
 // value across them with one register swap (no trip through LDS).
 __device__ __forceinline__ float xhalf_max(float v) {
@@ -325,19 +317,50 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     const T* __restrict__ Q, int64_t qs0, int64_t qs1, int64_t qs2,
     const T* __restrict__ Kp, int64_t kp0, int64_t kp1, const T* __restrict__ Vp, int64_t vp0, int64_t vp1,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ kcnt,
-    T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int zero_dropped,
+    T* __restrict__ O, int n, int npad, int ntq, int ug, int BH, int Hq, int Hkv, float c, int out_compact, int compute_blocks,
     int t_per_batch, int v_in_place)
 {
     using C = AttnCfg<T, D, NW, QB>;
     constexpr int kBM = C::BM, kNT = C::NT, kRW = 32 * QB;   // queries per workgroup, threads, queries per wave
     extern __shared__ __attribute__((aligned(16))) char smem[];
     // Workgroup -> (unit group, query tile, unit in group, head of the KV group), in that order of
-    // significance; heavy (late) query tiles first inside a group.  A group holds just enough KV heads
-    // to fill the chip a few times over (one for long GQA sequences, many for short MHA ones): the
-    // chip then works through few KV heads at a time, so every XCD's L2 (workgroups are dealt
-    // round-robin to the 8 XCDs) holds little more than the K / V^T it is using, while the light tail
-    // of one group overlaps the heavy start of the next.
+    // significance; heavy (late) query tiles first inside a group.  A group holds enough KV heads to
+    // fill the chip several times over (a few for long GQA sequences, many for short MHA ones): the
+    // chip then works through few KV heads at a time, so the caches hold little more than the K / V
+    // in use, while the light tail of one group overlaps the heavy start of the next.  The last query
+    // tile of a head runs for as long as all its kept keys take; a group must hold many times the
+    // chip's resident workgroups for that one not to end alone.
     const int G = Hq / Hkv, NU = BH / G;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
+    if (blockIdx.x >= (unsigned)compute_blocks) {
+        // Outputs of dropped tokens are zero rows.  The workgroups after the last attention workgroup
+        // each clear the dropped rows of one head inside one span of kFillSpan positions; they are
+        // dispatched last, into the slots that the light end of the attention work leaves idle.
+        const int f = blockIdx.x - compute_blocks, s = f / BH, fbh = f - s * BH;
+        const int fb = fbh / Hq, fu = fb * Hkv + (fbh - fb * Hq) / G;
+        const int32_t* ft = idx + (int64_t)(t_per_batch ? fb : fu) * n;
+        const int fk = kcnt ? max(0, min(kcnt[t_per_batch ? fb : fu], n)) : n;
+        const int p0 = s * kFillSpan, p1 = min(n, p0 + kFillSpan);
+        int* kept = reinterpret_cast<int*>(smem);            // [kFillSpan]
+        for (int e = tid; e < kFillSpan; e += kNT) kept[e] = 0;
+        int lo = 0, hi = fk;                                 // first kept row at or after p0 (T ascends)
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (ft[mid] < p0) lo = mid + 1; else hi = mid;
+        }
+        __syncthreads();
+        for (int e = lo + tid; e < min(fk, lo + kFillSpan); e += kNT) {
+            const int pos = ft[e];
+            if (pos >= p0 && pos < p1) kept[pos - p0] = 1;
+        }
+        __syncthreads();
+        constexpr int CPR = D * Elem<T>::kBytes / 16;
+        const uintx4 z = {0, 0, 0, 0};
+        char* base = reinterpret_cast<char*>(O + ((int64_t)fbh * n + p0) * D);
+        for (int q = tid; q < (p1 - p0) * CPR; q += kNT)
+            if (!kept[q / CPR]) store16(base + (int64_t)q * 16, z);
+        return;
+    }
     const int full = ug * ntq * G;                           // workgroups of a full group
     const int ngroups = (NU + ug - 1) / ug;
     const int grp = min((int)(blockIdx.x / full), ngroups - 1);
@@ -347,36 +370,10 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     const int u = grp * ug + rr / G, hg = rr % G;
     const int b = u / Hkv, g = u - b * Hkv, head = g * G + hg, bh = b * Hq + head;
     const int i0 = (ntq - 1 - tile_rev) * kBM;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
     const int32_t* tidx = idx ? idx + (int64_t)(t_per_batch ? b : u) * n : nullptr;   // this unit's T
     int kk = kcnt ? kcnt[t_per_batch ? b : u] : n;
     kk = max(0, min(kk, n));
-    if (i0 >= kk) {
-        if (zero_dropped && i0 == 0) zero_rows<T, D>(O, bh, n, 0, n, tid, kNT);   // nothing kept at all
-        return;
-    }
-    if (zero_dropped) {
-        // Outputs of dropped tokens are zero rows.  This workgroup clears the dropped positions that
-        // lie before each of its kept rows; the tile holding the last kept row also clears the tail.
-        int* tpos = reinterpret_cast<int*>(smem);            // [kBM + 1], dead before the first tile is staged
-        for (int e = tid; e <= kBM; e += kNT) {
-            const int r = i0 - 1 + e;                        // entry e: position of kept row i0 - 1 + e
-            tpos[e] = r < 0 ? -1 : (r < kk ? tidx[r] : n);
-        }
-        __syncthreads();
-        if (i0 + kBM == kk) zero_rows<T, D>(O, bh, n, tpos[kBM] + 1, n, tid, kNT);   // tail after a full last tile
-#pragma unroll
-        for (int half = 0; half < kBM / 64; ++half) {
-            const int gi = half * 64 + lane;
-            unsigned long long open = __ballot(tpos[gi + 1] - tpos[gi] > 1);
-            while (open) {                                   // wave-uniform walk over the non-empty gaps
-                const int gsel = half * 64 + __builtin_ctzll(open);
-                open &= open - 1;
-                zero_rows<T, D>(O, bh, n, tpos[gsel] + 1, tpos[gsel + 1], tid, kNT);
-            }
-        }
-        __syncthreads();                                     // tpos is overwritten by the first K tile
-    }
+    if (i0 >= kk) return;
     // kept-token coordinates of this lane's QB queries, their positions, their Q fragments
     int qrow[QB], qpos[QB];
     uintx4 qf[QB][C::CH];
@@ -610,16 +607,22 @@ static int launch_flash(const void* Q, const void* K, const zipvl_dims& d, const
         const int ntq = (d.n + C::BM - 1) / C::BM;
         const int64_t blocks = (int64_t)ntq * BH;
         const int G = d.Hq / d.Hkv;
-        int ug = (4096 / (NW * QB)) / (ntq * G);                  // KV heads per scheduling group (see the kernel)
+        // KV heads per scheduling group (see the kernel): about eight waves of workgroups on the chip, so
+        // that the longest workgroup (the last query tile) is a small part of a group even when only a
+        // fraction of the tiles is kept, but no more K / V than a quarter of the 256 MiB last-level cache
+        const int64_t unit_bytes = 2 * (int64_t)npad * D * Elem<T>::kBytes;
+        int ug = (int)std::min<int64_t>((16384 / (NW * QB)) / ((int64_t)ntq * G), (64ll << 20) / unit_bytes);
         ug = ug < 1 ? 1 : ug;
-        if (blocks > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
-        hipLaunchKernelGGL((flash_kept_kernel<T, D, NW, QB>), dim3((unsigned)blocks), dim3(C::NT),
+        // full-size output of a sparse call: one more workgroup per (head, span of positions) clears dropped rows
+        const int64_t fill = (!out_compact && idx) ? (int64_t)BH * ((d.n + kFillSpan - 1) / kFillSpan) : 0;
+        if (blocks + fill > 0x7fffffffLL) return set_error(ZIPVL_ESHAPE, "sparse_prefill: %lld workgroups exceed the grid limit", (long long)blocks);
+        hipLaunchKernelGGL((flash_kept_kernel<T, D, NW, QB>), dim3((unsigned)(blocks + fill)), dim3(C::NT),
             C::LDS_BYTES, st, (const T*)Q, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             skip_k ? (const T*)K : Kp, skip_k ? d.k_strides[0] : (int64_t)d.Hkv * npad * D,
             skip_k ? d.k_strides[1] : (int64_t)npad * D,
             skip_v ? (const T*)V : Vp, skip_v ? d.v_strides[0] : (int64_t)d.Hkv * npad * D,
             skip_v ? d.v_strides[1] : (int64_t)npad * D, idx, k, (T*)O, d.n, npad, ntq, ug, BH, d.Hq, d.Hkv,
-            scale * kLog2e, out_compact, (!out_compact && idx) ? 1 : 0, t_per_batch, skip_v);
+            scale * kLog2e, out_compact, (int)blocks, t_per_batch, skip_v);
     }
     return check_launch("flash_kept");
 }
