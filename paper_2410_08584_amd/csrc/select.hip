@@ -4,19 +4,20 @@
 // tau * total, then top-k by the normalised score".  Neither step needs the
 // sorted sequence itself:
 //   * the first crossing of the sorted cumulative sum is found by a radix
-//     descent over the 32-bit order-preserving image of the fp32 scores: per
-//     8-bit digit, an LDS histogram of counts and of exact integer sums
-//     (floor(x * 2^40), so the result is independent of summation order),
+//     descent over the 31-bit order-preserving image of the fp32 scores, in
+//     8-bit digits: per digit, an LDS histogram of counts and of exact integer
+//     sums (floor(x * 2^40), so the result is independent of summation order),
 //     a descending wave-shuffle scan over the 256 bins, and the bin where the
 //     running sum crosses the target; after four digits the remaining
 //     candidates are equal and the count follows by one integer division;
 //   * the top-k set is {score > v*} plus the lowest-indexed ties at v*, where
 //     v* is the k-th largest value, found by the same descent on counts;
-//   * the set is written in ascending position by a ballot-ranked stream
-//     compaction (each wave owns a contiguous span of positions).
-// One 1024-thread workgroup per selection unit.  Up to n = 26624 the order-preserving keys of
+//   * the set is written in ascending position: every thread classifies 32
+//     consecutive positions into two bit masks, a workgroup-wide scan of the
+//     mask populations gives each thread its output offset.
+// One 1024-thread workgroup per selection unit.  Up to n = 27648 the order-preserving keys of
 // the vector in use are held in LDS (read from memory once, coalesced); longer vectors are
-// re-read per digit.
+// re-read per digit and pass through LDS block by block for the emission.
 #include <atomic>
 
 #include "launch.h"
@@ -25,17 +26,19 @@ namespace zipvl {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kRep = 16;              // histogram replicas (lane % 16) against same-address atomics
+constexpr int kSelMaxLdsKeys = 27648;      // 108 KiB of keys beside the 32 KiB histogram
+constexpr int kSelPre = kSelMaxLdsKeys / kSelThreads;   // keys per thread of a vector held in LDS
+constexpr int kSelRep = 16, kSelRepStride = 257;    // histogram replicas and their spacing in slots
 
 struct SelShared {
-    uint32_t cnt[256 * kRep];
-    unsigned long long sum[256 * kRep];
+    unsigned long long hist[kSelRep * kSelRepStride];   // packed (count, integer sum) slots, or plain 32-bit counts
+    unsigned long long folded[256];
+    uint32_t wave_cnt[kSelWaves];
+    uint32_t wave_eq[kSelWaves];
     unsigned long long target;
     unsigned long long base_sum;
     uint32_t base_cnt;
     uint32_t sel_digit;
-    uint32_t wave_gt[kSelWaves];
-    uint32_t wave_eq[kSelWaves];
     int k;
 };
 
@@ -74,7 +77,6 @@ struct Keys {
             for (int j = threadIdx.x; j < n; j += kSelThreads) f(j, orderable(x[j]));
         }
     }
-    __device__ __forceinline__ uint32_t at(int j) const { return lds ? lds[j] : orderable(x[j]); }
 };
 
 __device__ __forceinline__ void fill_keys(uint32_t* dst, const float* __restrict__ x, int n) {
@@ -87,12 +89,15 @@ __device__ __forceinline__ unsigned long long fixed40_of_key(uint32_t key) {
 }
 
 // One descent over the 31 key bits in four digits, exponent byte first (8 + 8 + 8 + 7 bits).  The
-// first digit sees every element and uses kRep histogram replicas; later digits only see the
-// elements that share the prefix and use one.  WITH_SUM: a histogram slot packs the element count
-// (bits 41..63) over the integer score sum (bits 0..40, sum of a unit < 2^41), one LDS atomic per
-// element, and the descent crosses on the sum (target fixed after the first digit from the grand
-// total); otherwise slots are plain counts and the descent crosses on cnt_target.
+// first two digits see many elements and spread them over kRep histogram replicas chosen by the
+// lane (replica r of digit v sits at slot r * 257 + v: the lanes of a wave that share a digit hit
+// different banks, and a fold over the replicas reads consecutive slots); later digits only see the
+// few elements that share the prefix and use one replica.  WITH_SUM: a histogram slot packs the
+// element count (bits 41..63) over the integer score sum (bits 0..40, sum of a unit < 2^41), one LDS
+// atomic per element, and the descent crosses on the sum (target fixed after the first digit from
+// the grand total); otherwise slots are plain counts and the descent crosses on cnt_target.
 constexpr int kSumBits = 41;
+constexpr int kRep = kSelRep, kRepStride = kSelRepStride;
 
 template <bool WITH_SUM>
 __device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
@@ -100,45 +105,59 @@ __device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
                               unsigned long long& base_sum_out, bool& degenerate)
 {
     const int tid = threadIdx.x;
+    uint32_t* cnt_hist = reinterpret_cast<uint32_t*>(sh.hist);
     uint32_t prefix = 0, mask = 0, base_cnt = 0;
     unsigned long long base_sum = 0;
     degenerate = false;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = pass < 3 ? 23 - 8 * pass : 0;
         const uint32_t dmask = pass < 3 ? 255u : 127u;
-        const int rep = pass == 0 ? kRep : 1;
-        for (int i = tid; i < 256 * rep; i += kSelThreads) {
-            if (WITH_SUM) sh.sum[i] = 0; else sh.cnt[i] = 0;
+        const bool replicated = pass < 2;
+        const int slots = replicated ? kRep * kRepStride : 256;
+        const int rep_off = replicated ? (tid & (kRep - 1)) * kRepStride : 0;
+        for (int i = tid; i < slots; i += kSelThreads) {
+            if (WITH_SUM) sh.hist[i] = 0; else cnt_hist[i] = 0;
         }
         __syncthreads();
         keys.for_each([&](int, uint32_t key) {
             if ((key & mask) == prefix) {
-                const int slot = ((key >> shift) & dmask) * rep + (tid & (rep - 1));
-                if (WITH_SUM) atomicAdd(&sh.sum[slot], (1ull << kSumBits) + fixed40_of_key(key));
-                else atomicAdd(&sh.cnt[slot], 1u);
+                const int slot = rep_off + ((key >> shift) & dmask);
+                if (WITH_SUM) atomicAdd(&sh.hist[slot], (1ull << kSumBits) + fixed40_of_key(key));
+                else atomicAdd(&cnt_hist[slot], 1u);
             }
         });
         __syncthreads();
+        if (replicated) {                                   // fold the replicas of bin `tid` into replica 0
+            if (tid < 256) {
+                uint32_t cc = 0;
+                unsigned long long ss = 0;
+#pragma unroll
+                for (int r = 0; r < kRep; ++r) {
+                    if (WITH_SUM) ss += sh.hist[r * kRepStride + tid];   // count and sum fields add without carry between them
+                    else cc += cnt_hist[r * kRepStride + tid];
+                }
+                if (WITH_SUM) sh.folded[tid] = ss; else reinterpret_cast<uint32_t*>(sh.folded)[tid] = cc;
+            }
+            __syncthreads();
+        }
         if (tid < 64) {
-            // lane l owns bins 255-4l .. 252-4l (descending value order): fold the replicas, then scan
+            // lane l owns bins 255-4l .. 252-4l (descending value order)
+            const unsigned long long* h64 = replicated ? sh.folded : sh.hist;
+            const uint32_t* h32 = reinterpret_cast<const uint32_t*>(h64);
             uint32_t c[4], lc = 0;
             unsigned long long s[4], ls = 0;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int bin = 255 - (4 * tid + t);
-                uint32_t cc = 0;
-                unsigned long long ss = 0;
-                for (int r = 0; r < rep; ++r) {
-                    if (WITH_SUM) {
-                        const unsigned long long v = sh.sum[bin * rep + r];
-                        cc += (uint32_t)(v >> kSumBits);
-                        ss += v & ((1ull << kSumBits) - 1ull);
-                    } else {
-                        cc += sh.cnt[bin * rep + r];
-                    }
+                if (WITH_SUM) {
+                    const unsigned long long v = h64[bin];
+                    c[t] = (uint32_t)(v >> kSumBits);
+                    s[t] = v & ((1ull << kSumBits) - 1ull);
+                } else {
+                    c[t] = h32[bin];
+                    s[t] = 0;
                 }
-                c[t] = cc; s[t] = ss;
-                lc += cc; ls += ss;
+                lc += c[t]; ls += s[t];
             }
             uint32_t ic = lc;
             unsigned long long is = ls;
@@ -194,7 +213,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out, int keys_in_lds)
 {
     __shared__ SelShared sh;
-    extern __shared__ uint32_t lds_keys[];             // n entries when keys_in_lds
+    extern __shared__ uint32_t lds_keys[];             // kSelMaxLdsKeys entries
     const int u = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* mass = mass_all + (int64_t)u * n;
@@ -210,6 +229,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     // ---- how many (Eq. (7)) ----
     Keys mk{keys_in_lds ? lds_keys : nullptr, mass, n};
     if (keys_in_lds) { fill_keys(lds_keys, mass, n); __syncthreads(); }
+    // the second vector is requested now and waits in registers while the first descent runs
+    const bool second_vector = keys_in_lds && rank != mass;
+    float pre[kSelPre];
+    if (second_vector) {
+#pragma unroll
+        for (int q = 0; q < kSelPre; ++q) pre[q] = rank[min(tid + q * kSelThreads, n - 1)];   // independent loads
+    }
     int k;
     {
         uint32_t prefix, base_cnt;
@@ -237,7 +263,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 
     // ---- which (Eq. (9)): k-th largest normalised score v*, ties to the lower index ----
     Keys rk{keys_in_lds ? lds_keys : nullptr, rank, n};
-    if (keys_in_lds && rank != mass) { fill_keys(lds_keys, rank, n); __syncthreads(); }
+    if (second_vector) {
+#pragma unroll
+        for (int q = 0; q < kSelPre; ++q) {
+            const int j = tid + q * kSelThreads;
+            if (j < n) lds_keys[j] = orderable(pre[q]);
+        }
+        __syncthreads();
+    }
     uint32_t vstar, cnt_gt;
     {
         unsigned long long unused;
@@ -245,47 +278,77 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         radix_descent<false>(rk, tau, (uint32_t)k, sh, vstar, cnt_gt, unused, dg);
     }
     const uint32_t need_eq = (uint32_t)k - cnt_gt;     // ties at v* that are kept (>= 1)
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-    // ---- ascending emission: wave w owns positions [w*seg, (w+1)*seg) ----
-    const int seg = (((n + kSelWaves - 1) / kSelWaves) + 63) & ~63;
-    const int j0 = wave * seg, j1 = min(n, j0 + seg);
-    uint32_t wgt = 0, weq = 0;
-#pragma unroll 4
-    for (int j = j0 + lane; j - lane < j1; j += 64) {
-        const uint32_t key = (j < j1) ? rk.at(j) : 0u;
-        wgt += __popcll(__ballot(j < j1 && key > vstar));
-        weq += __popcll(__ballot(j < j1 && key == vstar));
-    }
-    if (lane == 0) { sh.wave_gt[wave] = wgt; sh.wave_eq[wave] = weq; }
-    __syncthreads();
-    uint32_t gt_before = 0, eq_before = 0;
-    for (int w = 0; w < wave; ++w) { gt_before += sh.wave_gt[w]; eq_before += sh.wave_eq[w]; }
-#pragma unroll 4
-    for (int j = j0 + lane; j - lane < j1; j += 64) {
-        const uint32_t key = (j < j1) ? rk.at(j) : 0u;
-        const bool gt = j < j1 && key > vstar;
-        const bool eq = j < j1 && key == vstar;
-        const unsigned long long bg = __ballot(gt), be = __ballot(eq);
-        const uint32_t my_eq_rank = eq_before + __popcll(be & lt_mask);
-        const bool keep = gt || (eq && my_eq_rank < need_eq);
-        const unsigned long long bk = __ballot(keep);
-        if (keep) {
-            const uint32_t pos = gt_before + min(eq_before, need_eq) + __popcll(bk & lt_mask);
-            idx[pos] = j;
+    // ---- ascending emission, one block of positions (as many as LDS holds) at a time ----
+    uint32_t gt_run = 0, eq_run = 0;                   // elements above / at v* in the blocks before
+    for (int b0 = 0; b0 < n; b0 += kSelMaxLdsKeys) {
+        const int bn = min(kSelMaxLdsKeys, n - b0);
+        if (!keys_in_lds) {
+            __syncthreads();
+            fill_keys(lds_keys, rank + b0, bn);
+            __syncthreads();
         }
-        gt_before += __popcll(bg);
-        eq_before += __popcll(be);
+        // thread t classifies positions [32 t, 32 t + 32) of the block; the rotation by the lane
+        // spreads the 64 reads of a wave over the banks
+        const int base = tid * 32;
+        uint32_t gm = 0, em = 0;
+        if (base < bn) {
+#pragma unroll 8
+            for (int cc = 0; cc < 32; ++cc) {
+                const int p = (cc + lane) & 31;
+                if (base + p < bn) {
+                    const uint32_t key = lds_keys[base + p];
+                    gm |= (key > vstar ? 1u : 0u) << p;
+                    em |= (key == vstar ? 1u : 0u) << p;
+                }
+            }
+        }
+        const uint32_t cg = __popc(gm), ce = __popc(em);
+        uint32_t ig = cg, ie = ce;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t tg = __shfl_up(ig, o), te = __shfl_up(ie, o);
+            if (lane >= o) { ig += tg; ie += te; }
+        }
+        if (lane == 63) { sh.wave_cnt[wave] = ig; sh.wave_eq[wave] = ie; }
+        __syncthreads();
+        uint32_t gt_before = gt_run + (ig - cg), eq_before = eq_run + (ie - ce), tot_g = 0, tot_e = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < kSelWaves; ++w2) {
+            const uint32_t wg = sh.wave_cnt[w2], we = sh.wave_eq[w2];
+            if (w2 < wave) { gt_before += wg; eq_before += we; }
+            tot_g += wg; tot_e += we;
+        }
+        // of this thread's ties, the lowest-indexed `allow` are kept
+        const uint32_t allow = need_eq > eq_before ? need_eq - eq_before : 0u;
+        uint32_t ek = em;
+        if (allow < ce) {
+            ek = 0;
+            uint32_t rest = em;
+            for (uint32_t a2 = 0; a2 < allow; ++a2) {
+                const uint32_t low = rest & (0u - rest);
+                ek |= low;
+                rest ^= low;
+            }
+        }
+        uint32_t km = gm | ek;
+        uint32_t out = gt_before + min(eq_before, need_eq);
+        while (km) {
+            const int p = __builtin_ctz(km);
+            km &= km - 1;
+            idx[out++] = b0 + base + p;
+        }
+        gt_run += tot_g;
+        eq_run += tot_e;
     }
 }
-
-constexpr int kSelMaxLdsKeys = 27648;      // 108 KiB of keys beside the 48 KiB of histograms
 
 int launch_select(const float* mass, const float* rank, int units, int n, double tau,
                   int32_t* idx, int32_t* k, hipStream_t st)
 {
     const int in_lds = n <= kSelMaxLdsKeys ? 1 : 0;
-    const size_t dyn = in_lds ? (size_t)n * sizeof(uint32_t) : 0;
+    // the key area also stages the blocks of a longer vector for the emission
+    const size_t dyn = (size_t)(in_lds ? n : kSelMaxLdsKeys) * sizeof(uint32_t);
     static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
