@@ -49,8 +49,10 @@ __device__ __forceinline__ void load_row_frags(const T* row, int h, uintx4 (&f)[
 // PASS 2: mass / rank of the workgroup's keys, from bias[bh * 64 + probe] = max * c + log2(sum)
 // GCT = query heads whose probe rows are staged in LDS at once (1 when the group has a single head: fewer
 // staging registers and a smaller LDS footprint, so more workgroups per CU hide the load latency)
+// bf16: at least three workgroups per CU; the register budget that follows keeps the accumulators in architectural VGPRs,
+// where the vector ALU reads them without copies.
 template <typename T, int D, int PASS, int NB, int GCT>
-__global__ __launch_bounds__(kScoreThreads) void score_pass_kernel(
+__global__ __launch_bounds__(kScoreThreads, (Elem<T>::kBytes == 2 ? 3 : 1)) void score_pass_kernel(
     const T* __restrict__ Q, const T* __restrict__ K,
     int64_t qs0, int64_t qs1, int64_t qs2, int64_t ks0, int64_t ks1, int64_t ks2,
     ProbeList probes, int m, int n, int n_eff, float c, float2* __restrict__ partial, int nsplit,
