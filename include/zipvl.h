@@ -55,6 +55,7 @@ extern "C" {
 #define ZIPVL_OP_QUANTIZE_KV    5
 #define ZIPVL_OP_DECODE_Q       6  /* dims->n = cap_hi + cap_lo + cap_tail */
 #define ZIPVL_OP_SCORE_ALL_ROWS 7
+#define ZIPVL_OP_DECODE_STEP    8  /* dims->n = cap */
 
 /* flags of zipvl_sparse_prefill */
 #define ZIPVL_OUT_FULL            0  /* O is [B,Hq,n,d]; rows of dropped tokens are written as zeros */
@@ -194,6 +195,21 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
                       void* o, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * One decode step in one launch: zipvl_kv_append followed by zipvl_decode_attn (Eq. (4), Eq. (5) /
+ * Algorithm 2), with the same results: the new row is written at row len[u] and takes part in the
+ * attention, len[u] is incremented afterwards; a full cache (len == cap) is left unchanged and attended
+ * as it is.  Arguments as in those two calls.
+ * ws [device]: zipvl_workspace_bytes(ZIPVL_OP_DECODE_STEP, dims (n = cap), 0) bytes, 16-byte aligned.  Its
+ * first 4 * B * Hkv bytes are per-unit arrival counters: they must be zero before the first call that
+ * uses this workspace, every call leaves them zero, and nothing else may write there between calls
+ * (two calls that overlap on one workspace race).  Groups larger than 8 query heads per KV head run the
+ * two separate kernels inside this call.
+ */
+int zipvl_decode_step(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
+                      const void* v_new, const zipvl_dims* dims, float softmax_scale, void* o,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Mixed-precision KV cache keyed by the important set.  Paper: Section 5.3.1 and Table 3 (important
  * tokens quantised to 4 bits, the other tokens to 2 bits; nothing is evicted).  The quantiser itself is
  * not given there; the one used is uniform, asymmetric, per row (one token of one KV head), in fp32:
@@ -261,7 +277,8 @@ int zipvl_decode_attn_q(const void* q, const zipvl_qtensor* Kq, const zipvl_qten
 #define ZIPVL_K_ALLROWS_COLSUM 16
 #define ZIPVL_K_PROBE_MFMA     17
 #define ZIPVL_K_PROBE_READ     18
-#define ZIPVL_K_COUNT          19
+#define ZIPVL_K_DECODE_STEP    19
+#define ZIPVL_K_COUNT          20
 int zipvl_timing_enable(int on);
 int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
 

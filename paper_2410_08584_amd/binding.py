@@ -12,10 +12,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libzipvl.so"
 
 OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT, T_PER_BATCH = 0, 1, 2, 4
-OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q, OP_SCORE_ALL_ROWS = 1, 2, 3, 4, 5, 6, 7
+OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q, OP_SCORE_ALL_ROWS, OP_DECODE_STEP = 1, 2, 3, 4, 5, 6, 7, 8
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
-           "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
+           "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn", "zipvl_decode_step",
            "zipvl_timing_enable", "zipvl_timing_read", "zipvl_probe_mfma", "zipvl_probe_stream_read")
 
 
@@ -77,12 +77,15 @@ def load_library():
     lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
     lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
                                       C.c_size_t, vp]
+    lib.zipvl_decode_step.argtypes = [vp, vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), C.c_float, vp, vp,
+                                      C.c_size_t, vp]
     lib.zipvl_timing_enable.argtypes = [C.c_int]
     lib.zipvl_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.zipvl_timing_enable.restype = C.c_int
     lib.zipvl_timing_read.restype = C.c_int
-    for name in ("zipvl_score", "zipvl_score_all_rows", "zipvl_select", "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv",
-                 "zipvl_kv_append", "zipvl_decode_attn"):
+    for name in ("zipvl_score", "zipvl_score_all_rows", "zipvl_select", "zipvl_share_scores", "zipvl_quantize_kv",
+                 "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn",
+                 "zipvl_decode_step"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -274,6 +277,26 @@ def zipvl_decode_attn(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lengt
     return o
 
 
+def decode_step_workspace(B: int, Hq: int, Hkv: int, cap: int, d: int, dtype_like: torch.Tensor) -> torch.Tensor:
+    """A zero-filled workspace for zipvl_decode_step (its arrival counters must start at zero)."""
+    dm = dims_of(None, None, None, B=B, Hq=Hq, Hkv=Hkv, n=cap, d=d, dtype=_dtype_code(dtype_like))
+    return torch.zeros(max(256, workspace_bytes(OP_DECODE_STEP, dm)), dtype=torch.uint8, device=dtype_like.device)
+
+
+def zipvl_decode_step(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, length: torch.Tensor,
+                      k_new: torch.Tensor, v_new: torch.Tensor, softmax_scale: float, *, B: int, Hq: int, Hkv: int,
+                      ws: torch.Tensor, o: Optional[torch.Tensor] = None):
+    """Append k_new / v_new and attend, one launch; ws from decode_step_workspace (kept between steps)."""
+    lib = load_library()
+    units, cap, d = Kc.shape
+    dm = dims_of(None, None, None, B=B, Hq=Hq, Hkv=Hkv, n=cap, d=d, dtype=_dtype_code(Kc))
+    if o is None:
+        o = torch.empty((B * Hq, d), dtype=q.dtype, device=q.device)
+    _check(lib.zipvl_decode_step(_ptr(q), _ptr(Kc), _ptr(Vc), _ptr(length), int(cap), _ptr(k_new), _ptr(v_new),
+                                 C.byref(dm), float(softmax_scale), _ptr(o), _ptr(ws), ws.numel(), _stream()))
+    return o
+
+
 class QCache:
     """Device arrays of the mixed-precision cache built by zipvl_quantize_kv."""
 
@@ -340,7 +363,8 @@ def zipvl_decode_attn_q(q: torch.Tensor, cache: QCache, softmax_scale: float, *,
 
 KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
            "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal", "share_scores",
-           "token_slots", "quantize_rows", "decode_q_partial", "allrows_lse", "allrows_colsum", "probe_mfma", "probe_read")
+           "token_slots", "quantize_rows", "decode_q_partial", "allrows_lse", "allrows_colsum", "probe_mfma", "probe_read",
+           "decode_step")
 
 
 def zipvl_probe_peaks(device="cuda:0", iters: int = 4096, read_mib: int = 4096):

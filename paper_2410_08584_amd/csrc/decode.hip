@@ -13,6 +13,10 @@ namespace zipvl {
 
 constexpr int kDecMaxSplit = 64;
 
+template <typename T> __device__ __forceinline__ T to_out(float x);
+template <> __device__ __forceinline__ float to_out<float>(float x) { return x; }
+template <> __device__ __forceinline__ __bf16 to_out<__bf16>(float x) { return (__bf16)x; }
+
 // One cached row against the GT queries of the group: kf / vf are this lane's EPL elements of the row.
 template <int EPL, int GT>
 __device__ __forceinline__ void attend_row(bool valid, const float (&kf)[EPL], const float (&vf)[EPL],
@@ -55,8 +59,14 @@ __device__ __forceinline__ void load_queries(const T* q, int b, int g, int G, in
 
 // The 4 waves' states in red[wave][head][o[D], m, l] -> the workgroup's partial state.
 // partial layout: [(unit*G + head_in_group) * nsplit + split][D + 2]  (o[D], m, l), log2 domain
-template <int D, int GT>
+// COHERENT: the partial state is read by another workgroup of the same launch (possibly on another XCD,
+// whose L2 is not coherent with this one's): written through with device-scope stores.
+template <int D, int GT, bool COHERENT = false>
 __device__ __forceinline__ void combine_waves(float (&red)[4][GT][D + 2], int u, int G, int gbase, int split, int nsplit, float* part) {
+    auto put = [](float* p, float v) {
+        if constexpr (COHERENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *p = v;
+    };
     for (int wi = threadIdx.x; wi < GT * D; wi += 256) {
         const int t = wi / D, dd = wi - t * D;
         if (gbase + t >= G) continue;
@@ -73,13 +83,13 @@ __device__ __forceinline__ void combine_waves(float (&red)[4][GT][D + 2], int u,
             }
         }
         float* dst = part + (((int64_t)u * G + gbase + t) * nsplit + split) * (D + 2);
-        dst[dd] = acc;
-        if (dd == 0) { dst[D] = M; dst[D + 1] = lsum; }
+        put(dst + dd, acc);
+        if (dd == 0) { put(dst + D, M); put(dst + D + 1, lsum); }
     }
 }
 
 // Merge the 4 row groups of every wave, then the 4 waves, and write the workgroup's partial state.
-template <int D, int GT>
+template <int D, int GT, bool COHERENT = false>
 __device__ __forceinline__ void write_partial(float (&m)[GT], float (&l)[GT], float (&o)[GT][D / 16], float (&red)[4][GT][D + 2],
                                               int u, int G, int gbase, int split, int nsplit, float* part) {
     constexpr int EPL = D / 16;
@@ -101,7 +111,7 @@ __device__ __forceinline__ void write_partial(float (&m)[GT], float (&l)[GT], fl
         }
     }
     __syncthreads();
-    combine_waves<D, GT>(red, u, G, gbase, split, nsplit, part);
+    combine_waves<D, GT, COHERENT>(red, u, G, gbase, split, nsplit, part);
 }
 
 // rows [r_begin, r_end) of a segment of L rows that split `split` of nsplit handles (multiples of 16 rows)
@@ -157,6 +167,96 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(
         attend_row<EPL, GT>(valid, kf, vf, qv, m, l, o);
     }
     write_partial<D, GT>(m, l, o, red, u, G, gbase, split, nsplit, part);
+}
+
+// ---------------------------------------------------------------- one launch per decode step
+// Append and attention of Algorithm 2 in one kernel: the workgroup of the last split also takes the new
+// row (from k_new / v_new, which it copies into the cache at row len), and the workgroup that finishes
+// last for a unit (arrival counter in the workspace) merges the unit's partial states, writes the
+// output, advances len and clears the counter.  Every workgroup of a unit has read len before it
+// arrives at the counter, so the update cannot be seen by a reader of the old value.
+template <typename T, int EPL> struct alignas(sizeof(T) * EPL > 16 ? 16 : sizeof(T) * EPL) RawChunk { T v[EPL]; };
+
+template <typename T, int D, int GT>
+__global__ __launch_bounds__(256) void decode_step_kernel(
+    const T* __restrict__ q, T* __restrict__ Kc, T* __restrict__ Vc, int32_t* __restrict__ len, int cap,
+    const T* __restrict__ k_new, const T* __restrict__ v_new, int Hq, int Hkv, float c,
+    float* __restrict__ part, int nsplit, unsigned* __restrict__ arrived, T* __restrict__ out)
+{
+    constexpr int EPL = D / 16;
+    __shared__ float red[4][GT][D + 2];
+    __shared__ int is_last;
+    const int G = Hq / Hkv;
+    const int split = blockIdx.x, u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, sub = lane & 15, rg = lane >> 4;
+    const int Lraw = len[u];
+    const bool room = Lraw >= 0 && Lraw < cap;               // a full cache is left unchanged, as by the append call
+    const int L = max(0, min(Lraw, cap));
+    int r_begin, r_end;
+    split_range(L, split, nsplit, r_begin, r_end);
+
+    float qv[GT][EPL];
+    load_queries<T, D, GT>(q, b, g, G, Hq, 0, sub, c, qv);
+    float m[GT], l[GT], o[GT][EPL];
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+        m[t] = -INFINITY; l[t] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[t][e] = 0.f;
+    }
+    const T* Kb = Kc + (int64_t)u * cap * D + sub * EPL;
+    const T* Vb = Vc + (int64_t)u * cap * D + sub * EPL;
+#pragma unroll 2
+    for (int r = r_begin + w * 4 + rg; r - rg - w * 4 < r_end; r += 16) {
+        const bool valid = r < r_end;
+        const int rr = valid ? r : r_begin;
+        float kf[EPL], vf[EPL];
+        RowChunk<T, EPL>::load(Kb + (int64_t)rr * D, kf);
+        RowChunk<T, EPL>::load(Vb + (int64_t)rr * D, vf);
+        attend_row<EPL, GT>(valid, kf, vf, qv, m, l, o);
+    }
+    if (room && split == nsplit - 1 && w == 0) {            // wave-uniform: the appended row
+        using Raw = RawChunk<T, EPL>;
+        const Raw kr = *reinterpret_cast<const Raw*>(k_new + (int64_t)u * D + sub * EPL);
+        const Raw vr = *reinterpret_cast<const Raw*>(v_new + (int64_t)u * D + sub * EPL);
+        float kf[EPL], vf[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) { kf[e] = (float)kr.v[e]; vf[e] = (float)vr.v[e]; }
+        if (rg == 0) {
+            *reinterpret_cast<Raw*>(Kc + ((int64_t)u * cap + L) * D + sub * EPL) = kr;
+            *reinterpret_cast<Raw*>(Vc + ((int64_t)u * cap + L) * D + sub * EPL) = vr;
+        }
+        attend_row<EPL, GT>(rg == 0, kf, vf, qv, m, l, o);
+    }
+    write_partial<D, GT, true>(m, l, o, red, u, G, 0, split, nsplit, part);
+
+    // The partial state went out with device-scope (write-through) stores: once they have completed
+    // (vmcnt 0) it is visible to every XCD, and only then is this workgroup counted.  A release fence
+    // would do the same by writing back the whole L2, 150 us per launch here.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) is_last = atomicAdd(&arrived[u], 1u) == (unsigned)(nsplit - 1);
+    __syncthreads();
+    if (!is_last) return;
+    auto get = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    for (int wi = tid; wi < G * D; wi += 256) {
+        const int t = wi / D, dd = wi - t * D;
+        const float* p = part + ((int64_t)u * G + t) * nsplit * (D + 2);
+        float M = -INFINITY;
+        for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, get(p + sp * (D + 2) + D));
+        float acc = 0.f, lsum = 0.f;
+        if (M > -INFINITY)
+            for (int sp = 0; sp < nsplit; ++sp) {
+                const float a = fast_exp2(get(p + sp * (D + 2) + D) - M);
+                acc += get(p + sp * (D + 2) + dd) * a;
+                lsum += get(p + sp * (D + 2) + D + 1) * a;
+            }
+        out[((int64_t)u * G + t) * D + dd] = to_out<T>(lsum > 0.f ? acc / lsum : 0.f);
+    }
+    if (tid == 0) {
+        if (room) len[u] = Lraw + 1;
+        arrived[u] = 0u;                                     // ready for the next step
+    }
 }
 
 // ---------------------------------------------------------------- mixed-precision cache
@@ -477,10 +577,6 @@ __global__ __launch_bounds__(256) void decode_q4_partial_kernel(
     combine_waves<D, GT>(red, u, G, gbase, split, nsplit, part);
 }
 
-template <typename T> __device__ __forceinline__ T to_out(float x);
-template <> __device__ __forceinline__ float to_out<float>(float x) { return x; }
-template <> __device__ __forceinline__ __bf16 to_out<__bf16>(float x) { return (__bf16)x; }
-
 template <typename T, int D>
 __global__ void decode_combine_kernel(const float* __restrict__ part, int nsplit, T* __restrict__ o)
 {
@@ -573,6 +669,49 @@ static int launch_decode_q_t(const void* q, const zipvl_qtensor& Kq, const zipvl
     hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(d.B * d.Hq), dim3(D), 0, st,
         (const float*)ws, nsplit, (T*)o);
     return check_launch("decode_combine");
+}
+
+static size_t step_counter_bytes(const zipvl_dims& d) { return ((size_t)d.B * d.Hkv * sizeof(unsigned) + 255) / 256 * 256; }
+
+size_t decode_step_workspace_bytes(const zipvl_dims& d, int cap) {
+    return step_counter_bytes(d) + decode_workspace_bytes(d, cap);
+}
+
+template <typename T, int D>
+static int launch_decode_step_t(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
+                                const void* v_new, const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st)
+{
+    const int G = d.Hq / d.Hkv, units = d.B * d.Hkv, nsplit = decode_splits(d, cap);
+    unsigned* arrived = (unsigned*)ws;
+    float* part = (float*)((char*)ws + step_counter_bytes(d));
+    if (G > 8) {                                            // several passes over the cache per step: not fused
+        int rc = launch_kv_append(Kc, Vc, len, cap, k_new, v_new, d, st);
+        if (rc) return rc;
+        return launch_decode_attn(q, Kc, Vc, len, cap, d, scale, o, part, st);
+    }
+    const float c = scale * kLog2e;
+    dim3 grid(nsplit, units);
+    KernelTimer tm(ZIPVL_K_DECODE_STEP, st);
+#define ZIPVL_STEP(GT)                                                                               \
+    hipLaunchKernelGGL((decode_step_kernel<T, D, GT>), grid, dim3(256), 0, st, (const T*)q, (T*)Kc, (T*)Vc, len, cap, \
+        (const T*)k_new, (const T*)v_new, d.Hq, d.Hkv, c, part, nsplit, arrived, (T*)o)
+    if (G >= 5) ZIPVL_STEP(8);
+    else if (G >= 3) ZIPVL_STEP(4);
+    else if (G == 2) ZIPVL_STEP(2);
+    else ZIPVL_STEP(1);
+#undef ZIPVL_STEP
+    return check_launch("decode_step");
+}
+
+int launch_decode_step(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
+                       const void* v_new, const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st)
+{
+    if (d.dtype == ZIPVL_BF16) {
+        if (d.d == 128) return launch_decode_step_t<__bf16, 128>(q, Kc, Vc, len, cap, k_new, v_new, d, scale, o, ws, st);
+        return launch_decode_step_t<__bf16, 64>(q, Kc, Vc, len, cap, k_new, v_new, d, scale, o, ws, st);
+    }
+    if (d.d == 128) return launch_decode_step_t<float, 128>(q, Kc, Vc, len, cap, k_new, v_new, d, scale, o, ws, st);
+    return launch_decode_step_t<float, 64>(q, Kc, Vc, len, cap, k_new, v_new, d, scale, o, ws, st);
 }
 
 int launch_decode_attn_q(const void* q, const zipvl_qtensor& Kq, const zipvl_qtensor& Vq, const int32_t* len_hi,

@@ -39,6 +39,10 @@ size_t decode_workspace_bytes(const zipvl_dims& d, int cap);
 int launch_decode_attn(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
                        const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);
 
+size_t decode_step_workspace_bytes(const zipvl_dims& d, int cap);
+int launch_decode_step(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
+                       const void* v_new, const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);
+
 size_t allrows_workspace_bytes(const zipvl_dims& d);
 int launch_score_all_rows(const void* Q, const void* K, const zipvl_dims& d, float scale,
                           float* mass, float* rank, void* ws, hipStream_t st);

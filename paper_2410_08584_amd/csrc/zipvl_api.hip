@@ -111,6 +111,7 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m) {
         case ZIPVL_OP_QUANTIZE_KV: return quantize_workspace_bytes(*dims);
         case ZIPVL_OP_DECODE_Q: return decode_workspace_bytes(*dims, dims->n);
         case ZIPVL_OP_SCORE_ALL_ROWS: return allrows_workspace_bytes(*dims);
+        case ZIPVL_OP_DECODE_STEP: return decode_step_workspace_bytes(*dims, dims->n);
         default: set_error(ZIPVL_EUNSUPPORTED, "zipvl_workspace_bytes: unknown op %d", op); return 0;
     }
 }
@@ -256,6 +257,28 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
     if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
     if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
     return launch_decode_attn(q, Kc, Vc, len, cap, *dims, softmax_scale, o, ws, (hipStream_t)stream);
+}
+
+int zipvl_decode_step(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
+                      const void* v_new, const zipvl_dims* dims, float softmax_scale, void* o,
+                      void* ws, size_t ws_bytes, void* stream)
+{
+    const char* fn = "zipvl_decode_step";
+    int rc = check_dims(fn, dims, false, false, false);
+    if (rc) return rc;
+    ZIPVL_REQUIRE_PTR(fn, q);
+    ZIPVL_REQUIRE_PTR(fn, Kc);
+    ZIPVL_REQUIRE_PTR(fn, Vc);
+    ZIPVL_REQUIRE_PTR(fn, k_new);
+    ZIPVL_REQUIRE_PTR(fn, v_new);
+    ZIPVL_REQUIRE_PTR(fn, o);
+    if (!len) return set_error(ZIPVL_EINVAL, "%s: len is NULL", fn);
+    if (cap < 1) return set_error(ZIPVL_EINVAL, "%s: cap = %d must be positive", fn, cap);
+    if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return set_error(ZIPVL_EINVAL, "%s: softmax_scale must be positive and finite", fn);
+    const size_t need = decode_step_workspace_bytes(*dims, cap);
+    if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
+    if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
+    return launch_decode_step(q, Kc, Vc, len, cap, k_new, v_new, *dims, softmax_scale, o, ws, (hipStream_t)stream);
 }
 
 static int check_qtensor(const char* fn, const char* what, const zipvl_qtensor* t) {

@@ -691,3 +691,51 @@ def test_decode_append_and_attention(dtype, d, Hq, Hkv):
             assert Kc[u, lens[u]].to(torch.float32).cpu().numpy().tobytes() == kn[u].tobytes()
     say(f"  worst |do| = {worst:.3e}")
     assert worst <= ATOL_OUT[dtype]
+
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 4, 4), ("bf16", 128, 14, 2), ("f32", 64, 4, 2), ("bf16", 64, 3, 1),
+                                            ("f32", 128, 8, 1), ("bf16", 128, 18, 2)])
+def test_decode_step_one_launch_matches_append_then_attention(dtype, d, Hq, Hkv):
+    """Three consecutive fused steps (the arrival counters must clear themselves) against the oracle's
+    append-then-attend, with an empty unit, a long one and one that is full from the second step on."""
+    say(f"decode_step dtype={dtype} d={d} Hq={Hq} Hkv={Hkv}")
+    B, cap = 2, 1300
+    G = Hq // Hkv
+    units = B * Hkv
+    w = make_custom(B, Hq, Hkv, cap, d, dtype, seed=33)
+    Kc = dev(w.K, dtype).reshape(units, cap, d).clone()
+    Vc = dev(w.V, dtype).reshape(units, cap, d).clone()
+    lens = [0, 1299, 640, 17][:units] + [5] * max(0, units - 4)
+    ln = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    r = np.random.Generator(np.random.PCG64(34))
+    from workloads import round_to_bf16
+    cast = round_to_bf16 if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    Kh = [w.K.reshape(units, cap, d)[u].copy() for u in range(units)]
+    Vh = [w.V.reshape(units, cap, d)[u].copy() for u in range(units)]
+    ws = z.decode_step_workspace(B, Hq, Hkv, cap, d, Kc)
+    worst = 0.0
+    for step in range(3):
+        q = cast(r.standard_normal((B * Hq, d)).astype(np.float32) * 2)
+        kn = cast(r.standard_normal((units, d)).astype(np.float32))
+        vn = cast(r.standard_normal((units, d)).astype(np.float32))
+        o = z.zipvl_decode_step(dev(q, dtype), Kc, Vc, ln, dev(kn, dtype), dev(vn, dtype), w.scale, B=B, Hq=Hq, Hkv=Hkv, ws=ws)
+        torch.cuda.synchronize()
+        oh = host64(o)
+        new_lens = list(lens)
+        for u in range(units):
+            if lens[u] < cap:
+                Kh[u][lens[u]] = kn[u]; Vh[u][lens[u]] = vn[u]
+                new_lens[u] = lens[u] + 1
+        for b in range(B):
+            for h in range(Hq):
+                u = b * Hkv + h // G
+                ref = oz.decode_attention(q[b * Hq + h], Kh[u], Vh[u], new_lens[u], w.scale)
+                worst = max(worst, np.abs(oh[b * Hq + h] - ref).max())
+        lens = new_lens
+        assert ln.cpu().tolist() == lens
+        for u in range(units):                                # the caches hold exactly the oracle's rows
+            assert Kc[u, :lens[u]].to(torch.float32).cpu().numpy().tobytes() == Kh[u][:lens[u]].astype(np.float32).tobytes()
+            assert Vc[u, :lens[u]].to(torch.float32).cpu().numpy().tobytes() == Vh[u][:lens[u]].astype(np.float32).tobytes()
+    assert int(ws[:4 * units].view(torch.int32).abs().sum().item()) == 0      # counters left at zero
+    say(f"  worst |do| = {worst:.3e}")
+    assert worst <= ATOL_OUT[dtype]
