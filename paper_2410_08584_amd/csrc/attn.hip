@@ -21,11 +21,14 @@
 //          coming tiles are issued one at a time in its first half.  Causality is
 //          the plain lower triangle in kept-token coordinates because T is
 //          ascending.  Query rows are gathered by idx on load, output rows are
-//          scattered by idx on store, and the rows of dropped tokens between a
-//          workgroup's kept rows are cleared by that workgroup (no separate fill).
+//          scattered by idx on store.  The zero rows of dropped tokens are written
+//          by extra workgroups at the end of the same grid (one per head and span
+//          of positions), which run in the slots the thinning end of the
+//          attention work leaves idle.
 // The kept count k lives on the device: the grid covers the worst case (k = n)
 // and workgroups beyond a unit's k exit at once; heavy (late) query tiles are
-// scheduled first.
+// scheduled first, over all KV heads of a schedule group, because the longest
+// workgroup (all k keys) lasts a large part of the whole launch.
 #include <algorithm>
 #include <atomic>
 
