@@ -293,14 +293,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         const int base = tid * 32;
         uint32_t gm = 0, em = 0;
         if (base < bn) {
-#pragma unroll 8
+            // all 32 reads are issued at once (index clamped, the mask bit predicated instead)
+            uint32_t key[32];
+#pragma unroll
+            for (int cc = 0; cc < 32; ++cc) key[cc] = lds_keys[min(base + ((cc + lane) & 31), bn - 1)];
+#pragma unroll
             for (int cc = 0; cc < 32; ++cc) {
                 const int p = (cc + lane) & 31;
-                if (base + p < bn) {
-                    const uint32_t key = lds_keys[base + p];
-                    gm |= (key > vstar ? 1u : 0u) << p;
-                    em |= (key == vstar ? 1u : 0u) << p;
-                }
+                const bool in = base + p < bn;
+                gm |= (in && key[cc] > vstar ? 1u : 0u) << p;
+                em |= (in && key[cc] == vstar ? 1u : 0u) << p;
             }
         }
         const uint32_t cg = __popc(gm), ce = __popc(em);
