@@ -154,6 +154,7 @@ int zipvl_share_scores(const float* mass, const float* rank, int B, int Hkv, int
  * For every query head h of unit u, with T = idx[u, 0..k[u]-1] (ascending):
  *   O[h, T_i] = sum_{j<=i} softmax_j( Q[h,T_i] . K[g,T_j] * softmax_scale ) V[g,T_j]
  * idx, k [device] as written by zipvl_select; both NULL = every token kept (dense).
+ * T must hold strictly ascending positions in [0, n) (not checked: the values live on the device).
  * flags: ZIPVL_OUT_FULL (default) | ZIPVL_OUT_COMPACT | ZIPVL_KV_ALREADY_COMPACT | ZIPVL_T_PER_BATCH
  * (with ZIPVL_T_PER_BATCH, T of unit u is idx[b, 0..k[b]-1]).
  * O [device] [B,Hq,n,d] contiguous, dtype as the inputs.
