@@ -45,6 +45,8 @@ def test_workspace_sizes(lib):
     assert z.workspace_bytes(z.OP_SELECT, dm) == 0
     assert z.workspace_bytes(z.OP_SCORE, dm, 64) > 0
     assert z.workspace_bytes(z.OP_DECODE, dm) > 0
+    # the fused decode step adds one 256-byte-rounded block of per-unit arrival counters in front of the partial states
+    assert z.workspace_bytes(z.OP_DECODE_STEP, dm) == z.workspace_bytes(z.OP_DECODE, dm) + 256
     assert z.workspace_bytes(99, dm) == 0 and "unknown op" in z.zipvl_last_error()
 
 
