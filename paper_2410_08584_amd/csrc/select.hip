@@ -39,6 +39,8 @@ struct SelShared {
     unsigned long long base_sum;
     uint32_t base_cnt;
     uint32_t sel_digit;
+    uint32_t sel_cnt;      // elements in the selected bin
+    uint32_t sole_key;     // the key of a bin's only element
     int k;
 };
 
@@ -191,6 +193,7 @@ __device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
                     sh.sel_digit = 255 - (4 * tid + t);
                     sh.base_cnt = rc;
                     sh.base_sum = rs;
+                    sh.sel_cnt = c[t];
                 }
                 rc += c[t];
                 rs += s[t];
@@ -202,6 +205,16 @@ __device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
         mask |= dmask << shift;
         base_cnt = sh.base_cnt;
         base_sum = sh.base_sum;
+        if (pass < 3 && sh.sel_cnt == 1u) {
+            // One element left under this prefix: the remaining digits are its own.  One sweep fetches the key
+            // (the counts and sums above it are already final) instead of a histogram pass per digit.
+            keys.for_each([&](int, uint32_t key) {
+                if ((key & mask) == prefix) sh.sole_key = key;
+            });
+            __syncthreads();
+            prefix = sh.sole_key;
+            break;
+        }
     }
     prefix_out = prefix;
     base_cnt_out = base_cnt;
