@@ -117,3 +117,14 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(b, "_LIB_NAME", "libzipvl_not_built.so")
     with pytest.raises(z.ZipvlError):
         b.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other count ends with a message and a non-zero status, before any GPU work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
