@@ -27,12 +27,19 @@ closed form for Q=0, one-hot scores, all-rows probes against a dense softmax
 taken with another library, brute-force subset enumeration for the selection,
 tie/permutation invariance, tau=1, monotonicity in tau, uniform closed form,
 masked-dense equivalence and running-mean closed form for the kept-token
-attention, head-averaged scores against the float64 mean and the single-head
+attention (whole product and row-at-a-time form alike), head-averaged scores against the float64 mean and the single-head
 case, the row quantiser against the nearest-grid-point definition, its
 half-step error bound and Table 3's compression ratios, torch SDPA for dense attention, Table 2/3 ratio accounting.
 Parity unpinned (our own readings, checked only for self-consistency): the
 per-KV-head granularity and group averaging, the zero padding value, the 2^40
-grid, and the synthetic kept ratios.
+grid, the synthetic kept ratios, and the parameter granularity assumed by
+kv_quant_compression (a group size fitted to Table 3's two ratios, not a value
+the paper states).
+Two functions, share_scores and quantize_rows, decide integers (a selection, a
+code) from floating point; both take those steps in fp32, the precision the
+GPU kernels use, so that the two sides decide alike.  That precision is a
+choice made here, not something the paper fixes; the quantiser is pinned
+against the float64 nearest-grid-point definition regardless.
 """
 from __future__ import annotations
 

@@ -13,7 +13,9 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzipvl.so")
 SOURCES = ["zipvl_api.hip", "score.hip", "select.hip", "attn.hip", "compact.hip", "decode.hip", "quant.hip", "allrows.hip", "peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # packed fp32 vector instructions off, for the device pass only (the host pass does not know the feature)
+         "-Xarch_device", "-Xclang", "-Xarch_device", "-target-feature",
+         "-Xarch_device", "-Xclang", "-Xarch_device", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
 
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "zipvl.h"
+#include "zipvl_bench.h"
 
 namespace zipvl {
 

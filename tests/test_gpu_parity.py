@@ -1,8 +1,8 @@
 """Parity of the HIP path (through the C ABI) against the CPU float64 oracle.
 
 Rules: kept count and kept index set are exact when the oracle's selection is
-fed the GPU's own fp32 scores; scores within 1e-6 + 1e-3*value (bf16 inputs)
-or 1e-7 + 1e-5*value (fp32 inputs); attention outputs within max-abs 2e-2
+fed the GPU's own fp32 scores; scores within 1e-9 + 1e-5*value (either input
+dtype: the oracle sees the exact device inputs); attention outputs within max-abs 2e-2
 (bf16) / 1e-4 (fp32) with the oracle evaluated on the GPU's index set;
 compaction bit-exact.
 """
@@ -38,12 +38,19 @@ def host64(t: torch.Tensor) -> np.ndarray:
 
 
 def score_tol(dtype):
-    return (1e-6, 1e-3) if dtype == "bf16" else (1e-7, 1e-5)
+    # The oracle is fed the exact device inputs, so bf16 storage adds nothing: products of bf16 values are
+    # exact in fp32 and both dtypes accumulate in fp32.  Relative error of a probability = ln 2 x the absolute
+    # error of its log2-domain exponent (about 2e-6 at |logit| <= 30) plus one ulp each for exp2 and log2.
+    return (1e-9, 1e-5)
+
+
+WORST_SCORE_ERR = {"rel": 0.0}       # largest |got - ref| / (1e-9/1e-5 + |ref|) seen in this process, for the log
 
 
 def assert_scores_close(got, ref, dtype, what):
     a, r = score_tol(dtype)
     err = np.abs(got - ref) - (a + r * np.abs(ref))
+    WORST_SCORE_ERR["rel"] = max(WORST_SCORE_ERR["rel"], float((np.abs(got - ref) / (a / r + np.abs(ref))).max()))
     assert err.max() <= 0, f"{what}: worst excess {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
 
 
@@ -165,6 +172,7 @@ def test_scores_match_oracle(case):
         assert_scores_close(mass[b], mo, dtype, "mass")
         assert_scores_close(rank[b], ro, dtype, "rank")
         np.testing.assert_allclose(mass[b].sum(axis=1), 1.0, atol=2e-5)
+    say(f"  worst relative score error so far {WORST_SCORE_ERR['rel']:.2e} (bound 1e-5)")
 
 
 # ------------------------------------------------------------------ attention
@@ -258,15 +266,38 @@ def test_attention_on_already_compacted_cache(n):
 
 
 # ------------------------------------------------------------------ whole layer
-def _layer_parity(w, tau, sample_rows=None, heads=None):
+def _edge_rows(p, r, extra):
+    """Kept-token rows at the edges of the attention kernel's tiling (128 queries per workgroup, 32 per
+    wave, 64 keys per tile): first and last rows of the first, a middle and the last query tile, rows on
+    both sides of 64-key tile edges, the last kept row, plus `extra` random rows."""
+    last_q, last_k, mid = (p - 1) // 128 * 128, (p - 1) // 64 * 64, (p // 2) // 128 * 128
+    cand = [0, 1, 31, 32, 63, 64, 65, 127, 128, 129, mid - 1, mid, mid + 63, mid + 64, mid + 127,
+            last_q - 1, last_q, last_k - 1, last_k, p - 2, p - 1]
+    cand = [c for c in cand if 0 <= c < p]
+    return np.unique(np.concatenate([np.array(cand, dtype=np.int64), r.integers(0, p, extra)]))
+
+
+def _layer_parity(w, tau, sample_rows=None, heads=None, whole_heads=()):
+    """Score, select, compaction and attention of one layer against the oracle.  The attention is run
+    twice: on the original K, V (the library gathers K[T], V[T] itself), and exactly as the benchmark's
+    step runs it - K and V read in place from the evicted cache (rows past k hold NaN), full-size output
+    with the dropped rows cleared by the kernel.  Both outputs meet the oracle on every checked row.
+    sample_rows=None: every row of the heads in `heads` (all heads when None).  Otherwise the tile-edge
+    rows plus `sample_rows` random ones of those heads, and every row of the heads in `whole_heads`."""
     spec = w.spec
     B, Hq, Hkv, n, d, dtype = w.Q.shape[0], spec.Hq, spec.Hkv, spec.n, spec.d, spec.dtype
     G = Hq // Hkv
     Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
     mass, rank = z.zipvl_score(Q, K, w.probe_pos, w.scale)
     idx, k = z.zipvl_select(mass, rank, tau)
-    Kc, Vc, ln = z.zipvl_compact_kv(K, V, idx, k, n)
-    O = z.zipvl_sparse_prefill(Q, K, V, idx, k, w.scale)
+    Kc = torch.full((B * Hkv, n, d), float("nan"), dtype=Q.dtype, device=DEV)
+    Vc = torch.full((B * Hkv, n, d), float("nan"), dtype=Q.dtype, device=DEV)
+    _, _, ln = z.zipvl_compact_kv(K, V, idx, k, n, Kc=Kc, Vc=Vc)
+    outs = {"gathered by the library": z.zipvl_sparse_prefill(Q, K, V, idx, k, w.scale)}
+    O2 = torch.full((B, Hq, n, d), 7.0, dtype=Q.dtype, device=DEV)      # poison: every row must be rewritten
+    z.zipvl_sparse_prefill(Q, Kc.view(B, Hkv, n, d), Vc.view(B, Hkv, n, d), idx, k, w.scale,
+                           z.OUT_FULL | z.KV_ALREADY_COMPACT, O=O2)
+    outs["evicted cache read in place (the benchmark's step)"] = O2
     torch.cuda.synchronize()
     mass_h, rank_h = mass.cpu().numpy(), rank.cpu().numpy()
     idx_h, k_h = idx.cpu().numpy(), k.cpu().numpy()
@@ -284,26 +315,35 @@ def _layer_parity(w, tau, sample_rows=None, heads=None):
             ko, vo, _ = oz.compact_kv(w.K[b, g], w.V[b, g], T)
             assert Kc[u, :p].to(torch.float32).cpu().numpy().tobytes() == ko.tobytes()
             assert Vc[u, :p].to(torch.float32).cpu().numpy().tobytes() == vo.tobytes()
-    worst = 0.0
+    worst = {name: 0.0 for name in outs}
     r = np.random.Generator(np.random.PCG64(77))
+    checked_rows = 0
     for b in range(B):
-        for h in (range(Hq) if heads is None else heads):
+        for h in (range(Hq) if heads is None else sorted(set(heads) | set(whole_heads))):
             g = h // G
             u = b * Hkv + g
             T = idx_h[u, :k_h[u]]
-            Oh = host64(O[b, h])
-            if sample_rows is None:
+            whole = sample_rows is None or h in whole_heads
+            if whole:
                 ref = oz.kept_token_attention(w.Q[b, h], w.K[b, g], w.V[b, g], T, w.scale)
-                worst = max(worst, np.abs(Oh - ref).max())
+                checked_rows += len(T)
             else:
-                rows = np.unique(np.concatenate([[0, len(T) - 1, min(127, len(T) - 1), min(128, len(T) - 1)],
-                                                 r.integers(0, len(T), sample_rows)]))
+                rows = _edge_rows(len(T), r, sample_rows)
                 ref = oz.kept_token_attention_rows(w.Q[b, h], w.K[b, g], w.V[b, g], T, rows, w.scale)
-                worst = max(worst, np.abs(Oh[T[rows]] - ref).max())
                 dropped = np.setdiff1d(np.arange(n), T)
-                assert not Oh[dropped].any(), "dropped rows must be zero"
-    say(f"  kept {100 * np.mean(kept):.1f}% (min {100 * min(kept):.1f}, max {100 * max(kept):.1f}); worst |dO| = {worst:.3e}")
-    assert worst <= ATOL_OUT[dtype]
+                checked_rows += len(rows)
+            for name, O in outs.items():
+                Oh = host64(O[b, h])
+                assert not np.isnan(Oh).any(), f"{name}: NaN in head {h}"
+                if whole:
+                    worst[name] = max(worst[name], np.abs(Oh - ref).max())       # dropped rows: ref is 0 there
+                else:
+                    worst[name] = max(worst[name], np.abs(Oh[T[rows]] - ref).max())
+                    assert not Oh[dropped].any(), f"{name}: dropped rows must be zero"
+    say(f"  kept {100 * np.mean(kept):.1f}% (min {100 * min(kept):.1f}, max {100 * max(kept):.1f}); {checked_rows} kept rows checked; "
+        + "; ".join(f"worst |dO| {name} = {v:.3e}" for name, v in worst.items()))
+    for name, v in worst.items():
+        assert v <= ATOL_OUT[dtype], name
     return kept
 
 
@@ -595,7 +635,7 @@ def test_layer_tau_one_is_dense_attention():
 def test_layer_cfg2_sampled():
     say("layer cfg2 (bf16, 32 heads, n=3072), sampled output rows")
     w = make_workload(2)
-    _layer_parity(w, w.tau, sample_rows=24, heads=[0, 13, 31])
+    _layer_parity(w, w.tau, sample_rows=8, heads=range(32), whole_heads=[0, 13, 31])
 
 
 def test_layer_cfg3_three_taus_selection_and_sampled_rows():
@@ -603,15 +643,15 @@ def test_layer_cfg3_three_taus_selection_and_sampled_rows():
     w = make_workload(3)
     ks = []
     for tau in w.spec.taus:
-        kept = _layer_parity(w, tau, sample_rows=8, heads=[7])
+        kept = _layer_parity(w, tau, sample_rows=4, heads=range(0, 40, 3), whole_heads=[7] if tau == w.tau else [])
         ks.append(np.mean(kept))
     assert ks[0] <= ks[1] <= ks[2]
 
 
 def test_layer_cfg4_headline_shape_sampled():
-    say("layer cfg4 (bf16 GQA 28/4, n=18432), sampled output rows")
+    say("layer cfg4 (bf16 GQA 28/4, n=18432): one whole query head per KV group, tile-edge rows of all 28 heads")
     w = make_workload(4)
-    _layer_parity(w, w.tau, sample_rows=12, heads=[0, 6, 27])
+    _layer_parity(w, w.tau, sample_rows=6, heads=range(28), whole_heads=[0, 9, 18, 27])
 
 
 def test_layer_beyond_the_benchmark_lengths_sampled():
@@ -621,13 +661,13 @@ def test_layer_beyond_the_benchmark_lengths_sampled():
 
 
 def test_layer_cfg5_first_and_last_layer_then_decode_on_evicted_cache():
-    say("layer cfg5 (bf16, 32 heads, n=8192), layers 0 and 31, batch slice of 1; then decode on the evicted cache")
+    say("layer cfg5 (bf16, 32 heads, n=8192), layers 0, 10, 21 and 31 of the ramp, batch slice of 1; then decode on the evicted cache")
     fracs = []
-    for layer in (0, 31):
+    for layer in (0, 10, 21, 31):
         w = make_workload(5, layer=layer, batch=1)
-        kept = _layer_parity(w, w.tau, sample_rows=6, heads=[3, 30])
+        kept = _layer_parity(w, w.tau, sample_rows=4, heads=[3, 17, 30], whole_heads=[30] if layer == 31 else [])
         fracs.append(np.mean(kept))
-    assert abs(fracs[0] - fracs[1]) > 0.05         # the spike ramp makes the kept ratio layer dependent
+    assert max(fracs) - min(fracs) > 0.05          # the spike ramp makes the kept ratio layer dependent
     # decode: two steps against the evicted cache of the last layer
     spec = w.spec
     Q, K, V = dev(w.Q, "bf16"), dev(w.K, "bf16"), dev(w.V, "bf16")

@@ -256,6 +256,32 @@ def test_kept_attention_zero_query_running_mean():
         np.testing.assert_allclose(O[t], V[T[: i + 1]].mean(axis=0), atol=1e-14)
 
 
+def test_kept_attention_rows_equal_the_whole_product_and_the_key_masked_softmax():
+    # The row-at-a-time form used for spot checks at sizes where the whole product is slow: it must be
+    # (a) the same rows of the gather-then-dense form, (b) the same rows of a full n x n softmax taken with
+    # torch in which the dropped keys are blocked, (c) the running mean of V[T] when Q = 0, and it must see
+    # the query's own key (row 0 returns V[T_0]) and nothing after it.
+    r = _rng(15)
+    n, d = 53, 8
+    Q, K, V = (r.standard_normal((n, d)) for _ in range(3))
+    T = np.sort(r.choice(n, 23, replace=False))
+    rows = np.array([0, 1, 7, 21, 22])
+    got = oz.kept_token_attention_rows(Q, K, V, T, rows, 0.3)
+    np.testing.assert_allclose(got, oz.kept_token_attention(Q, K, V, T, 0.3, compact_out=True)[rows], atol=1e-14)
+    keep = np.zeros(n, bool); keep[T] = True
+    S = torch.from_numpy(Q @ K.T * 0.3)
+    mask = torch.triu(torch.ones(n, n, dtype=torch.bool), 1) | torch.from_numpy(~keep)[None, :]
+    A = torch.softmax(S.masked_fill(mask, float("-inf")), 1).numpy()
+    np.testing.assert_allclose(got, (A @ V)[T[rows]], atol=1e-13)
+    np.testing.assert_array_equal(got[0], V[T[0]])
+    zero_q = oz.kept_token_attention_rows(np.zeros((n, d)), K, V, T, rows, 1.0)
+    for o, i in zip(zero_q, rows):
+        np.testing.assert_allclose(o, V[T[: i + 1]].mean(axis=0), atol=1e-14)
+    # a later key must not leak into an earlier row: changing V at T_22 leaves row 21 as it was
+    V2 = V.copy(); V2[T[22]] += 100.0
+    np.testing.assert_array_equal(oz.kept_token_attention_rows(Q, K, V2, T, rows[:4], 0.3), got[:4])
+
+
 def test_compaction_and_complement():
     r = _rng(13)
     K, V = r.standard_normal((20, 4)).astype(np.float32), r.standard_normal((20, 4)).astype(np.float32)
