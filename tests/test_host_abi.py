@@ -31,8 +31,9 @@ def _dims(B=1, Hq=4, Hkv=4, n=128, d=64, dtype=0, strides=None):
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "zipvl.h")).read()
-    declared = set(re.findall(r"\b(zipvl_[a-z_]+)\s*\(", header))
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
+    declared = set(re.findall(r"\b(zipvl_[a-z_0-9]+)\s*\(", header))
     assert declared == set(z.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
