@@ -196,6 +196,21 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
                       void* o, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * zipvl_decode_attn for callers that cannot allocate device memory or carry a workspace: code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and same results as zipvl_decode_attn, without ws / ws_bytes: the partial states of the split-KV kernels
+ * live in a fixed array of ZIPVL_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the
+ * process ends).  The call allocates and frees nothing.  Dims whose zipvl_workspace_bytes(ZIPVL_OP_DECODE)
+ * exceeds ZIPVL_STATIC_SCRATCH_BYTES are rejected with ZIPVL_ESHAPE before anything is launched.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it; calls ordered on one stream do not.  The array keeps the last call's contents;
+ * nothing in it has to be cleared between calls.
+ */
+#define ZIPVL_STATIC_SCRATCH_BYTES (8u << 20)
+int zipvl_decode_attn_static(const void* q, const void* Kc, const void* Vc, const int32_t* len,
+                             int32_t cap, const zipvl_dims* dims, float softmax_scale, void* o, void* stream);
+
+/*
  * One decode step in one launch: zipvl_kv_append followed by zipvl_decode_attn (Eq. (4), Eq. (5) /
  * Algorithm 2), with the same results: the new row is written at row len[u] and takes part in the
  * attention, len[u] is incremented afterwards; a full cache (len == cap) is left unchanged and attended

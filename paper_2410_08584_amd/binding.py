@@ -15,7 +15,7 @@ OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT, T_PER_BATCH = 0, 1, 2, 4
 OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q, OP_SCORE_ALL_ROWS, OP_DECODE_STEP = 1, 2, 3, 4, 5, 6, 7, 8
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
-           "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn", "zipvl_decode_step",
+           "zipvl_score_all_rows", "zipvl_share_scores", "zipvl_quantize_kv", "zipvl_decode_attn_q", "zipvl_sparse_prefill", "zipvl_compact_kv", "zipvl_kv_append", "zipvl_decode_attn", "zipvl_decode_attn_static", "zipvl_decode_step",
            "zipvl_timing_enable", "zipvl_timing_read", "zipvl_probe_mfma", "zipvl_probe_stream_read")
 
 
@@ -77,6 +77,8 @@ def load_library():
     lib.zipvl_kv_append.argtypes = [vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), vp]
     lib.zipvl_decode_attn.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp,
                                       C.c_size_t, vp]
+    lib.zipvl_decode_attn_static.argtypes = [vp, vp, vp, i32p, C.c_int32, C.POINTER(Dims), C.c_float, vp, vp]
+    lib.zipvl_decode_attn_static.restype = C.c_int
     lib.zipvl_decode_step.argtypes = [vp, vp, vp, i32p, C.c_int32, vp, vp, C.POINTER(Dims), C.c_float, vp, vp,
                                       C.c_size_t, vp]
     lib.zipvl_timing_enable.argtypes = [C.c_int]
@@ -274,6 +276,17 @@ def zipvl_decode_attn(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lengt
         ws = _workspace(workspace_bytes(OP_DECODE, dm), q.device)
     _check(lib.zipvl_decode_attn(_ptr(q), _ptr(Kc), _ptr(Vc), _ptr(length), int(cap), C.byref(dm),
                                  float(softmax_scale), _ptr(o), _ptr(ws), ws.numel(), _stream()))
+    return o
+
+
+def zipvl_decode_attn_static(q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, length: torch.Tensor,
+                             softmax_scale: float, *, B: int, Hq: int, Hkv: int, o: torch.Tensor):
+    """zipvl_decode_attn without a workspace (the library's built-in scratch array); `o` is the caller's."""
+    lib = load_library()
+    units, cap, d = Kc.shape
+    dm = dims_of(None, None, None, B=B, Hq=Hq, Hkv=Hkv, n=cap, d=d, dtype=_dtype_code(Kc))
+    _check(lib.zipvl_decode_attn_static(_ptr(q), _ptr(Kc), _ptr(Vc), _ptr(length), int(cap), C.byref(dm),
+                                        float(softmax_scale), _ptr(o), _stream()))
     return o
 
 

@@ -6,6 +6,8 @@
 // shuffles and keeps an online-softmax state per row group; row groups, waves
 // and finally splits are merged with the usual (max, sum, weighted output)
 // rule.  All query heads of a KV group are served from the same read.
+#include <mutex>
+
 #include "launch.h"
 #include "rowops.h"
 
@@ -726,6 +728,47 @@ int launch_decode_attn_q(const void* q, const zipvl_qtensor& Kq, const zipvl_qte
     if (d.d == 128) return launch_decode_q_t<float, 128>(ZIPVL_ARGS);
     return launch_decode_q_t<float, 64>(ZIPVL_ARGS);
 #undef ZIPVL_ARGS
+}
+
+// ---------------------------------------------------------------- decode attention without a caller workspace
+// The partial states of the split-KV kernels live in a fixed device array of this library instead of a
+// workspace argument, for callers that cannot allocate.  Every GPU holds its own copy of the array at its
+// own address: the address is looked up once per device (with that device current) and only that pointer
+// is ever handed to kernels.  Nothing in the array has to start at zero: every (unit, head, split) slot is
+// written by the partial kernel before the combine kernel of the same call reads it.
+constexpr size_t kStaticScratchBytes = ZIPVL_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return set_error(ZIPVL_EHIP, "decode_attn_static: hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return set_error(ZIPVL_EUNSUPPORTED, "decode_attn_static: device ordinal %d is beyond %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return set_error(ZIPVL_EHIP, "decode_attn_static: no device address for the scratch array: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ZIPVL_OK;
+}
+
+int launch_decode_attn_static(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
+                              const zipvl_dims& d, float scale, void* o, hipStream_t st)
+{
+    const size_t need = decode_workspace_bytes(d, cap);
+    if (need > kStaticScratchBytes)
+        return set_error(ZIPVL_ESHAPE, "decode_attn_static: these dims need %zu bytes of partial states, the built-in scratch holds %zu "
+                                       "(use zipvl_decode_attn with a workspace)", need, kStaticScratchBytes);
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc) return rc;
+    return launch_decode_attn(q, Kc, Vc, len, cap, d, scale, o, ws, st);
 }
 
 int launch_decode_attn(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,

@@ -39,6 +39,9 @@ size_t decode_workspace_bytes(const zipvl_dims& d, int cap);
 int launch_decode_attn(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
                        const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);
 
+int launch_decode_attn_static(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
+                              const zipvl_dims& d, float scale, void* o, hipStream_t st);
+
 size_t decode_step_workspace_bytes(const zipvl_dims& d, int cap);
 int launch_decode_step(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
                        const void* v_new, const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st);

@@ -259,6 +259,22 @@ int zipvl_decode_attn(const void* q, const void* Kc, const void* Vc, const int32
     return launch_decode_attn(q, Kc, Vc, len, cap, *dims, softmax_scale, o, ws, (hipStream_t)stream);
 }
 
+int zipvl_decode_attn_static(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
+                             const zipvl_dims* dims, float softmax_scale, void* o, void* stream)
+{
+    const char* fn = "zipvl_decode_attn_static";
+    int rc = check_dims(fn, dims, false, false, false);
+    if (rc) return rc;
+    ZIPVL_REQUIRE_PTR(fn, q);
+    ZIPVL_REQUIRE_PTR(fn, Kc);
+    ZIPVL_REQUIRE_PTR(fn, Vc);
+    ZIPVL_REQUIRE_PTR(fn, o);
+    if (!len) return set_error(ZIPVL_EINVAL, "%s: len is NULL", fn);
+    if (cap < 1) return set_error(ZIPVL_EINVAL, "%s: cap = %d must be positive", fn, cap);
+    if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return set_error(ZIPVL_EINVAL, "%s: softmax_scale must be positive and finite", fn);
+    return launch_decode_attn_static(q, Kc, Vc, len, cap, *dims, softmax_scale, o, (hipStream_t)stream);
+}
+
 int zipvl_decode_step(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
                       const void* v_new, const zipvl_dims* dims, float softmax_scale, void* o,
                       void* ws, size_t ws_bytes, void* stream)

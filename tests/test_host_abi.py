@@ -112,6 +112,14 @@ def test_prefill_compact_decode_reject_bad_arguments(lib):
     assert ap(FAKE, FAKE, FAKE, 0, FAKE, FAKE, C.byref(dm), None) == -1
 
 
+def test_decode_attn_static_rejects_dims_beyond_its_scratch(lib):
+    dm = _dims(B=256, Hq=128, Hkv=128, n=4096, d=128, dtype=1)     # 32768 heads x 520 bytes of partial state
+    assert z.workspace_bytes(z.OP_DECODE, dm) > (8 << 20)
+    rc = lib.zipvl_decode_attn_static(FAKE, FAKE, FAKE, FAKE, 4096, C.byref(dm), C.c_float(0.1), FAKE, None)
+    assert rc == -2 and "scratch" in z.zipvl_last_error()
+    assert lib.zipvl_decode_attn_static(FAKE, FAKE, FAKE, None, 4096, C.byref(_dims()), C.c_float(0.1), FAKE, None) == -1
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     import paper_2410_08584_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
