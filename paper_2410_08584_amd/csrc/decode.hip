@@ -1,11 +1,17 @@
 // Decode-phase attention against the (evicted) KV cache (Eq. (5); Algorithm 2).
 // Memory-bound: one query per head, every cached row read exactly once.
-// Split-KV: grid = (splits, units); inside a workgroup 16 lanes cover one
-// cached row (16 bytes each at d = 128 bf16), so a wave reads 4 rows per step
-// as full 256-byte lines, reduces the dot product over the 16 lanes with
-// shuffles and keeps an online-softmax state per row group; row groups, waves
-// and finally splits are merged with the usual (max, sum, weighted output)
-// rule.  All query heads of a KV group are served from the same read.
+// Split-KV: grid = (splits, units).  A split is a fixed number of cached rows
+// (chosen on the host from the capacity), and how many splits of a unit have
+// work follows from the length that lives on the device: a short (evicted)
+// cache occupies few workgroups, all of the same size, and the dispatcher
+// balances them.  Inside a workgroup 16 lanes cover one cached row (16 bytes
+// each at d = 128 bf16), so a wave reads 4 rows per step as full 256-byte
+// lines (the rows of the next step are requested before the current ones are
+// consumed), reduces the dot product over the 16 lanes with shuffles and keeps
+// an online-softmax state per row group; row groups, waves and finally splits
+// are merged with the usual (max, sum, weighted output) rule.  All query
+// heads of a KV group are served from the same read.
+#include <algorithm>
 #include <mutex>
 
 #include "launch.h"
@@ -132,21 +138,71 @@ __device__ __forceinline__ void split_range64(int L, int split, int nsplit, int&
     r_end = min(L, r_begin + per);
 }
 
+// Rows per split for a cache of `cap` rows: 256 for short caches, more for long ones so that a unit never
+// has more than kDecRowSplits splits (the merge reads one partial state per split).  A multiple of 16.
+constexpr int kDecRowSplits = 16;
+static inline int rows_per_split(int cap) {
+    const int per = ((cap + kDecRowSplits - 1) / kDecRowSplits + 15) & ~15;
+    return per < 256 ? 256 : per;        // 128 ... 512 rows measured within 5 % of each other on 2000-row caches
+}
+
+template <typename T, int EPL> struct alignas(sizeof(T) * EPL > 16 ? 16 : sizeof(T) * EPL) RawChunk { T v[EPL]; };
+
+template <typename T, int EPL>
+__device__ __forceinline__ void raw_to_floats(const RawChunk<T, EPL>& r, float (&f)[EPL]) {
+    RowChunk<T, EPL>::load(r.v, f);
+}
+
+// Rows [r_begin, r_end) of one unit against the GT queries in qv.  Row r comes from the cache, except row
+// `new_row` (>= 0 only in the fused step), which comes from k_new / v_new and is also written to the cache.
+// The 16 row groups of the workgroup take rows r_begin + g, r_begin + g + 16, ...; the loads of a group's next
+// row are in flight while the current one is consumed.
+template <typename T, int D, int GT>
+__device__ __forceinline__ void attend_rows(const T* Kb, const T* Vb, T* Kw, T* Vw, const T* kn, const T* vn, int new_row,
+                                            int r_begin, int r_end, int group, const float (&qv)[GT][D / 16],
+                                            float (&m)[GT], float (&l)[GT], float (&o)[GT][D / 16]) {
+    constexpr int EPL = D / 16;
+    using Raw = RawChunk<T, EPL>;
+    auto fetch = [&](int r, Raw& kr, Raw& vr) {
+        const int rr = r < r_end ? r : r_begin;             // clamped rows are loaded and ignored
+        const bool fresh = rr == new_row;
+        kr = *reinterpret_cast<const Raw*>(fresh ? kn : Kb + (int64_t)rr * D);
+        vr = *reinterpret_cast<const Raw*>(fresh ? vn : Vb + (int64_t)rr * D);
+    };
+    if (r_begin >= r_end) return;
+    Raw kc, vc;
+    int r = r_begin + group;
+    fetch(r, kc, vc);
+    for (int base = r_begin; base < r_end; base += 16, r += 16) {   // workgroup-uniform trip count
+        Raw kx = kc, vx = vc;
+        if (base + 16 < r_end) fetch(r + 16, kx, vx);
+        const bool valid = r < r_end;
+        if (valid && r == new_row) {
+            *reinterpret_cast<Raw*>(Kw + (int64_t)r * D) = kc;
+            *reinterpret_cast<Raw*>(Vw + (int64_t)r * D) = vc;
+        }
+        float kf[EPL], vf[EPL];
+        raw_to_floats<T, EPL>(kc, kf);
+        raw_to_floats<T, EPL>(vc, vf);
+        attend_row<EPL, GT>(valid, kf, vf, qv, m, l, o);
+        kc = kx; vc = vx;
+    }
+}
+
 template <typename T, int D, int GT>
 __global__ __launch_bounds__(256) void decode_partial_kernel(
     const T* __restrict__ q, const T* __restrict__ Kc, const T* __restrict__ Vc,
     const int32_t* __restrict__ len, int cap, int Hq, int Hkv, int gbase, float c,
-    float* __restrict__ part, int nsplit)
+    float* __restrict__ part, int rows, int max_splits)
 {
     constexpr int EPL = D / 16;
     __shared__ float red[4][GT][D + 2];
     const int G = Hq / Hkv;
     const int split = blockIdx.x, u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, sub = lane & 15, rg = lane >> 4;
-    int L = len[u];
-    L = max(0, min(L, cap));
-    int r_begin, r_end;
-    split_range(L, split, nsplit, r_begin, r_end);
+    const int L = max(0, min(len[u], cap));
+    const int r_begin = split * rows, r_end = min(L, r_begin + rows);
+    if (split > 0 && r_begin >= L) return;                  // split 0 always reports (an empty state when L = 0)
 
     float qv[GT][EPL];
     load_queries<T, D, GT>(q, b, g, G, Hq, gbase, sub, c, qv);
@@ -159,102 +215,126 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(
     }
     const T* Kb = Kc + (int64_t)u * cap * D + sub * EPL;
     const T* Vb = Vc + (int64_t)u * cap * D + sub * EPL;
-#pragma unroll 2
-    for (int r = r_begin + w * 4 + rg; r - rg - w * 4 < r_end; r += 16) {
-        const bool valid = r < r_end;
-        const int rr = valid ? r : r_begin;                 // r_begin < r_end inside the loop
-        float kf[EPL], vf[EPL];
-        RowChunk<T, EPL>::load(Kb + (int64_t)rr * D, kf);
-        RowChunk<T, EPL>::load(Vb + (int64_t)rr * D, vf);
-        attend_row<EPL, GT>(valid, kf, vf, qv, m, l, o);
+    attend_rows<T, D, GT>(Kb, Vb, nullptr, nullptr, nullptr, nullptr, -1, r_begin, r_end, w * 4 + rg, qv, m, l, o);
+    write_partial<D, GT>(m, l, o, red, u, G, gbase, split, max_splits, part);
+}
+
+// The partial states of one unit's splits -> its output rows.  One wave per head first turns the splits'
+// (max, sum) pairs into weights a_s / sum_s(a_s l_s), a_s = exp2(m_s - max), one split per lane; then every
+// thread accumulates one output element over the splits, eight independent loads at a time.
+// nsplit <= 64.  COHERENT: the states were written by other workgroups of the same launch.
+template <typename T, int D, bool COHERENT>
+__device__ __forceinline__ void merge_splits(const float* __restrict__ part, int u, int G, int nsplit, int max_splits,
+                                             float (&wgt)[8][64], T* __restrict__ out) {
+    auto get = [](const float* p) {
+        if constexpr (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else return *p;
+    };
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    for (int t0 = 0; t0 < G; t0 += 8) {                      // groups larger than 8 heads: 8 at a time
+        const int gt = min(8, G - t0);
+        __syncthreads();
+        for (int t = w; t < gt; t += 4) {
+            const float* p = part + ((int64_t)u * G + t0 + t) * max_splits * (D + 2);
+            const float ms = lane < nsplit ? get(p + lane * (D + 2) + D) : -INFINITY;
+            const float ls = lane < nsplit ? get(p + lane * (D + 2) + D + 1) : 0.f;
+            float M = ms;
+#pragma unroll
+            for (int off = 32; off; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+            const float a = M > -INFINITY ? fast_exp2(ms - M) : 0.f;
+            float tot = a * ls;
+#pragma unroll
+            for (int off = 32; off; off >>= 1) tot += __shfl_xor(tot, off);
+            wgt[t][lane] = tot > 0.f ? a / tot : 0.f;
+        }
+        __syncthreads();
+        for (int wi = tid; wi < gt * D; wi += 256) {
+            const int t = wi / D, dd = wi - t * D;
+            const float* p = part + ((int64_t)u * G + t0 + t) * max_splits * (D + 2) + dd;
+            float acc = 0.f;
+            for (int s0 = 0; s0 < nsplit; s0 += 8) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = get(p + (int64_t)min(s0 + j, nsplit - 1) * (D + 2));
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc = fmaf(s0 + j < nsplit ? wgt[t][s0 + j] : 0.f, v[j], acc);
+            }
+            out[((int64_t)u * G + t0 + t) * D + dd] = to_out<T>(acc);
+        }
     }
-    write_partial<D, GT>(m, l, o, red, u, G, gbase, split, nsplit, part);
+}
+
+// Splits of unit u that hold rows: from the device-resident length when `len` is given, else `fixed`.
+__device__ __forceinline__ int unit_splits(const int32_t* len, int u, int cap, int rows, int fixed) {
+    if (!len) return fixed;
+    const int L = max(0, min(len[u], cap));
+    return max(1, (L + rows - 1) / rows);
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_combine_kernel(const float* __restrict__ part, const int32_t* __restrict__ len,
+                                                             int cap, int rows, int nsplit_fixed, int max_splits, int G,
+                                                             T* __restrict__ o)
+{
+    __shared__ float wgt[8][64];
+    const int u = blockIdx.x;
+    merge_splits<T, D, false>(part, u, G, unit_splits(len, u, cap, rows, nsplit_fixed), max_splits, wgt, o);
 }
 
 // ---------------------------------------------------------------- one launch per decode step
-// Append and attention of Algorithm 2 in one kernel: the workgroup of the last split also takes the new
-// row (from k_new / v_new, which it copies into the cache at row len), and the workgroup that finishes
-// last for a unit (arrival counter in the workspace) merges the unit's partial states, writes the
-// output, advances len and clears the counter.  Every workgroup of a unit has read len before it
-// arrives at the counter, so the update cannot be seen by a reader of the old value.
-template <typename T, int EPL> struct alignas(sizeof(T) * EPL > 16 ? 16 : sizeof(T) * EPL) RawChunk { T v[EPL]; };
-
+// Append and attention of Algorithm 2 in one kernel.  The new row (k_new / v_new) becomes row len of the
+// cache: the workgroup whose split contains that row takes it from k_new / v_new in its place in the row
+// order (the arithmetic is that of the two separate calls) and stores it in the cache.  Every workgroup
+// of a unit - those without rows too - reads len and then arrives at a per-unit counter; the one that
+// arrives last merges the unit's partial states, writes the output, advances len and clears the counter.
+// Since all workgroups have read len before the last one arrives, the update cannot be seen by a reader of
+// the old value.
 template <typename T, int D, int GT>
 __global__ __launch_bounds__(256) void decode_step_kernel(
     const T* __restrict__ q, T* __restrict__ Kc, T* __restrict__ Vc, int32_t* __restrict__ len, int cap,
     const T* __restrict__ k_new, const T* __restrict__ v_new, int Hq, int Hkv, float c,
-    float* __restrict__ part, int nsplit, unsigned* __restrict__ arrived, T* __restrict__ out)
+    float* __restrict__ part, int rows, int max_splits, unsigned* __restrict__ arrived, T* __restrict__ out)
 {
     constexpr int EPL = D / 16;
     __shared__ float red[4][GT][D + 2];
+    __shared__ float wgt[8][64];
     __shared__ int is_last;
     const int G = Hq / Hkv;
     const int split = blockIdx.x, u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, sub = lane & 15, rg = lane >> 4;
     const int Lraw = len[u];
     const bool room = Lraw >= 0 && Lraw < cap;               // a full cache is left unchanged, as by the append call
-    const int L = max(0, min(Lraw, cap));
-    int r_begin, r_end;
-    split_range(L, split, nsplit, r_begin, r_end);
+    const int L0 = max(0, min(Lraw, cap));
+    const int L = L0 + (room ? 1 : 0);                       // rows attended: the new one included
+    const int r_begin = split * rows, r_end = min(L, r_begin + rows);
+    const int nsplit = max(1, (L + rows - 1) / rows);
 
-    float qv[GT][EPL];
-    load_queries<T, D, GT>(q, b, g, G, Hq, 0, sub, c, qv);
-    float m[GT], l[GT], o[GT][EPL];
+    if (split < nsplit) {
+        float qv[GT][EPL];
+        load_queries<T, D, GT>(q, b, g, G, Hq, 0, sub, c, qv);
+        float m[GT], l[GT], o[GT][EPL];
 #pragma unroll
-    for (int t = 0; t < GT; ++t) {
-        m[t] = -INFINITY; l[t] = 0.f;
+        for (int t = 0; t < GT; ++t) {
+            m[t] = -INFINITY; l[t] = 0.f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[t][e] = 0.f;
-    }
-    const T* Kb = Kc + (int64_t)u * cap * D + sub * EPL;
-    const T* Vb = Vc + (int64_t)u * cap * D + sub * EPL;
-#pragma unroll 2
-    for (int r = r_begin + w * 4 + rg; r - rg - w * 4 < r_end; r += 16) {
-        const bool valid = r < r_end;
-        const int rr = valid ? r : r_begin;
-        float kf[EPL], vf[EPL];
-        RowChunk<T, EPL>::load(Kb + (int64_t)rr * D, kf);
-        RowChunk<T, EPL>::load(Vb + (int64_t)rr * D, vf);
-        attend_row<EPL, GT>(valid, kf, vf, qv, m, l, o);
-    }
-    if (room && split == nsplit - 1 && w == 0) {            // wave-uniform: the appended row
-        using Raw = RawChunk<T, EPL>;
-        const Raw kr = *reinterpret_cast<const Raw*>(k_new + (int64_t)u * D + sub * EPL);
-        const Raw vr = *reinterpret_cast<const Raw*>(v_new + (int64_t)u * D + sub * EPL);
-        float kf[EPL], vf[EPL];
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) { kf[e] = (float)kr.v[e]; vf[e] = (float)vr.v[e]; }
-        if (rg == 0) {
-            *reinterpret_cast<Raw*>(Kc + ((int64_t)u * cap + L) * D + sub * EPL) = kr;
-            *reinterpret_cast<Raw*>(Vc + ((int64_t)u * cap + L) * D + sub * EPL) = vr;
+            for (int e = 0; e < EPL; ++e) o[t][e] = 0.f;
         }
-        attend_row<EPL, GT>(rg == 0, kf, vf, qv, m, l, o);
+        T* Kb = Kc + (int64_t)u * cap * D + sub * EPL;
+        T* Vb = Vc + (int64_t)u * cap * D + sub * EPL;
+        attend_rows<T, D, GT>(Kb, Vb, Kb, Vb, k_new + (int64_t)u * D + sub * EPL, v_new + (int64_t)u * D + sub * EPL,
+                              room ? L0 : -1, r_begin, r_end, w * 4 + rg, qv, m, l, o);
+        write_partial<D, GT, true>(m, l, o, red, u, G, 0, split, max_splits, part);
     }
-    write_partial<D, GT, true>(m, l, o, red, u, G, 0, split, nsplit, part);
 
     // The partial state went out with device-scope (write-through) stores: once they have completed
     // (vmcnt 0) it is visible to every XCD, and only then is this workgroup counted.  A release fence
     // would do the same by writing back the whole L2, 150 us per launch here.
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (tid == 0) is_last = atomicAdd(&arrived[u], 1u) == (unsigned)(nsplit - 1);
+    if (tid == 0) is_last = atomicAdd(&arrived[u], 1u) == gridDim.x - 1u;
     __syncthreads();
     if (!is_last) return;
-    auto get = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-    for (int wi = tid; wi < G * D; wi += 256) {
-        const int t = wi / D, dd = wi - t * D;
-        const float* p = part + ((int64_t)u * G + t) * nsplit * (D + 2);
-        float M = -INFINITY;
-        for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, get(p + sp * (D + 2) + D));
-        float acc = 0.f, lsum = 0.f;
-        if (M > -INFINITY)
-            for (int sp = 0; sp < nsplit; ++sp) {
-                const float a = fast_exp2(get(p + sp * (D + 2) + D) - M);
-                acc += get(p + sp * (D + 2) + dd) * a;
-                lsum += get(p + sp * (D + 2) + D + 1) * a;
-            }
-        out[((int64_t)u * G + t) * D + dd] = to_out<T>(lsum > 0.f ? acc / lsum : 0.f);
-    }
+    merge_splits<T, D, true>(part, u, G, nsplit, max_splits, wgt, out);
     if (tid == 0) {
         if (room) len[u] = Lraw + 1;
         arrived[u] = 0u;                                     // ready for the next step
@@ -308,7 +388,6 @@ __global__ __launch_bounds__(256) void decode_q_partial_kernel(
         const int L = max(0, min(len_hi[u], cap_hi));
         split_range(L, split, nsplit, r_begin, r_end);
         const int64_t base = (int64_t)u * cap_hi;
-#pragma unroll 2
         for (int r = r_begin + w * 4 + rg; r - rg - w * 4 < r_end; r += 16) {
             const bool valid = r < r_end;
             const int64_t row = base + (valid ? r : r_begin);
@@ -322,7 +401,6 @@ __global__ __launch_bounds__(256) void decode_q_partial_kernel(
         const int L = max(0, min(len_lo[u], cap_lo));
         split_range(L, split, nsplit, r_begin, r_end);
         const int64_t base = (int64_t)u * cap_lo;
-#pragma unroll 2
         for (int r = r_begin + w * 4 + rg; r - rg - w * 4 < r_end; r += 16) {
             const bool valid = r < r_end;
             const int64_t row = base + (valid ? r : r_begin);
@@ -579,23 +657,6 @@ __global__ __launch_bounds__(256) void decode_q4_partial_kernel(
     combine_waves<D, GT>(red, u, G, gbase, split, nsplit, part);
 }
 
-template <typename T, int D>
-__global__ void decode_combine_kernel(const float* __restrict__ part, int nsplit, T* __restrict__ o)
-{
-    const int bh = blockIdx.x, dd = threadIdx.x;            // units*G + head_in_group == b*Hq + head
-    const float* p = part + (int64_t)bh * nsplit * (D + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[s * (D + 2) + D]);
-    float acc = 0.f, lsum = 0.f;
-    if (M > -INFINITY)
-        for (int s = 0; s < nsplit; ++s) {
-            const float a = fast_exp2(p[s * (D + 2) + D] - M);
-            acc += p[s * (D + 2) + dd] * a;
-            lsum += p[s * (D + 2) + D + 1] * a;
-        }
-    o[(int64_t)bh * D + dd] = to_out<T>(lsum > 0.f ? acc / lsum : 0.f);
-}
-
 static int decode_splits(const zipvl_dims& d, int cap) {
     const int units = d.B * d.Hkv;
     int s = (1024 + units - 1) / units;
@@ -604,20 +665,23 @@ static int decode_splits(const zipvl_dims& d, int cap) {
     return s < 1 ? 1 : (s > kDecMaxSplit ? kDecMaxSplit : s);
 }
 
+static int row_splits(int cap) { const int r = rows_per_split(cap); return (cap + r - 1) / r; }
+
 size_t decode_workspace_bytes(const zipvl_dims& d, int cap) {
-    return (size_t)d.B * d.Hq * decode_splits(d, cap) * (d.d + 2) * sizeof(float);
+    const int s = std::max(decode_splits(d, cap), row_splits(cap));     // either split scheme fits
+    return (size_t)d.B * d.Hq * s * (d.d + 2) * sizeof(float);
 }
 
 template <typename T, int D>
 static int launch_decode_t(const void* q, const void* Kc, const void* Vc, const int32_t* len, int32_t cap,
                            const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st)
 {
-    const int G = d.Hq / d.Hkv, units = d.B * d.Hkv, nsplit = decode_splits(d, cap);
+    const int G = d.Hq / d.Hkv, units = d.B * d.Hkv, rows = rows_per_split(cap), max_splits = row_splits(cap);
     const float c = scale * kLog2e;
-    dim3 grid(nsplit, units);
+    dim3 grid(max_splits, units);
 #define ZIPVL_DEC(GT, GB)                                                                            \
     hipLaunchKernelGGL((decode_partial_kernel<T, D, GT>), grid, dim3(256), 0, st, (const T*)q,       \
-        (const T*)Kc, (const T*)Vc, len, cap, d.Hq, d.Hkv, GB, c, (float*)ws, nsplit)
+        (const T*)Kc, (const T*)Vc, len, cap, d.Hq, d.Hkv, GB, c, (float*)ws, rows, max_splits)
     for (int gb = 0; gb < G; gb += 8) {
         const int rem = G - gb;
         KernelTimer tm(ZIPVL_K_DECODE_PARTIAL, st);
@@ -630,8 +694,8 @@ static int launch_decode_t(const void* q, const void* Kc, const void* Vc, const 
     }
 #undef ZIPVL_DEC
     KernelTimer tm(ZIPVL_K_DECODE_COMBINE, st);
-    hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(d.B * d.Hq), dim3(D), 0, st,
-        (const float*)ws, nsplit, (T*)o);
+    hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(units), dim3(256), 0, st,
+        (const float*)ws, len, cap, rows, 0, max_splits, G, (T*)o);
     return check_launch("decode_combine");
 }
 
@@ -668,8 +732,8 @@ static int launch_decode_q_t(const void* q, const zipvl_qtensor& Kq, const zipvl
     }
 #undef ZIPVL_DECQ
     KernelTimer tm(ZIPVL_K_DECODE_COMBINE, st);
-    hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(d.B * d.Hq), dim3(D), 0, st,
-        (const float*)ws, nsplit, (T*)o);
+    hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(units), dim3(256), 0, st,
+        (const float*)ws, (const int32_t*)nullptr, 0, 1, nsplit, nsplit, G, (T*)o);
     return check_launch("decode_combine");
 }
 
@@ -683,7 +747,7 @@ template <typename T, int D>
 static int launch_decode_step_t(const void* q, void* Kc, void* Vc, int32_t* len, int32_t cap, const void* k_new,
                                 const void* v_new, const zipvl_dims& d, float scale, void* o, void* ws, hipStream_t st)
 {
-    const int G = d.Hq / d.Hkv, units = d.B * d.Hkv, nsplit = decode_splits(d, cap);
+    const int G = d.Hq / d.Hkv, units = d.B * d.Hkv, rows = rows_per_split(cap), max_splits = row_splits(cap);
     unsigned* arrived = (unsigned*)ws;
     float* part = (float*)((char*)ws + step_counter_bytes(d));
     if (G > 8) {                                            // several passes over the cache per step: not fused
@@ -692,11 +756,11 @@ static int launch_decode_step_t(const void* q, void* Kc, void* Vc, int32_t* len,
         return launch_decode_attn(q, Kc, Vc, len, cap, d, scale, o, part, st);
     }
     const float c = scale * kLog2e;
-    dim3 grid(nsplit, units);
+    dim3 grid(max_splits, units);
     KernelTimer tm(ZIPVL_K_DECODE_STEP, st);
 #define ZIPVL_STEP(GT)                                                                               \
     hipLaunchKernelGGL((decode_step_kernel<T, D, GT>), grid, dim3(256), 0, st, (const T*)q, (T*)Kc, (T*)Vc, len, cap, \
-        (const T*)k_new, (const T*)v_new, d.Hq, d.Hkv, c, part, nsplit, arrived, (T*)o)
+        (const T*)k_new, (const T*)v_new, d.Hq, d.Hkv, c, part, rows, max_splits, arrived, (T*)o)
     if (G >= 5) ZIPVL_STEP(8);
     else if (G >= 3) ZIPVL_STEP(4);
     else if (G == 2) ZIPVL_STEP(2);

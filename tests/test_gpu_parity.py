@@ -779,3 +779,46 @@ def test_decode_step_one_launch_matches_append_then_attention(dtype, d, Hq, Hkv)
     assert int(ws[:4 * units].view(torch.int32).abs().sum().item()) == 0      # counters left at zero
     say(f"  worst |do| = {worst:.3e}")
     assert worst <= ATOL_OUT[dtype]
+
+
+def test_decode_256_fused_steps_bit_identical_to_append_then_attention_at_the_stack_shape():
+    """zipvl_decode_step against zipvl_kv_append + zipvl_decode_attn over 256 consecutive steps at the 32-head,
+    batch-4 stack shape: outputs, lengths and caches must agree bit for bit at every step (the fused kernel
+    takes the new row in its place in the row order, so the arithmetic is the same).  Lengths are ragged,
+    cross split boundaries on the way, one unit starts empty and one fills up and must stay unchanged."""
+    say("decode_step x256 vs kv_append + decode_attn, B4 H32 d128")
+    B, H, d, cap, steps = 4, 32, 128, 2816, 256
+    units = B * H
+    g = torch.Generator(device=DEV); g.manual_seed(77)
+    Ka = torch.randn((units, cap, d), generator=g, device=DEV).to(torch.bfloat16)
+    Va = torch.randn((units, cap, d), generator=g, device=DEV).to(torch.bfloat16)
+    r = np.random.Generator(np.random.PCG64(78))
+    lens = r.integers(1500, 2500, units).astype(np.int32)
+    lens[0], lens[1], lens[2], lens[3] = 0, cap - 100, 255, 2559       # empty; fills up after 100 steps; next to split edges
+    la = torch.from_numpy(lens).to(DEV)
+    Kb, Vb, lb = Ka.clone(), Va.clone(), la.clone()
+    ws = z.decode_step_workspace(B, H, H, cap, d, Ka)
+    scale = 1.0 / math.sqrt(d)
+    oa = torch.empty((units, d), dtype=torch.bfloat16, device=DEV)
+    ob = torch.empty_like(oa)
+    for step in range(steps):
+        q = torch.randn((units, d), generator=g, device=DEV).to(torch.bfloat16)
+        kn = torch.randn((units, d), generator=g, device=DEV).to(torch.bfloat16)
+        vn = torch.randn((units, d), generator=g, device=DEV).to(torch.bfloat16)
+        z.zipvl_decode_step(q, Ka, Va, la, kn, vn, scale, B=B, Hq=H, Hkv=H, ws=ws, o=oa)
+        z.zipvl_kv_append(Kb, Vb, lb, kn, vn, B=B, Hkv=H)
+        z.zipvl_decode_attn(q, Kb, Vb, lb, scale, B=B, Hq=H, Hkv=H, o=ob)
+        torch.cuda.synchronize()
+        if not torch.equal(oa, ob):
+            bad = (oa != ob).any(dim=1).nonzero().flatten().tolist()
+            raise AssertionError(f"step {step}: outputs differ in units {bad[:8]} (lengths {la[bad[:8]].tolist()})")
+        assert torch.equal(la, lb), f"step {step}: lengths differ"
+    expect = np.minimum(lens.astype(np.int64) + steps, cap)
+    assert la.cpu().numpy().tolist() == expect.tolist()
+    assert torch.equal(Ka, Kb) and torch.equal(Va, Vb), "caches differ after 256 steps"
+    assert int(ws[:4 * units].view(torch.int32).abs().sum().item()) == 0          # counters left at zero
+    # and the last step meets the oracle (Eq. (5)) on a few units, the full one included
+    oh = host64(oa)
+    for u in (0, 1, 2, 3, 77):
+        ref = oz.decode_attention(host64(q[u]), host64(Ka[u]), host64(Va[u]), int(expect[u]), scale)
+        assert np.abs(oh[u] - ref).max() <= 2e-2
