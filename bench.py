@@ -40,6 +40,53 @@ def read_traffic(kernel: str, workload: str):
     return None
 
 
+TRAFFIC_NOTE = ("stored measurement: rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of this command, scaled by the copy calibration "
+                "(profiles/hbm_traffic.txt); not re-measured in this run")
+
+
+def cpu_baseline_stack(samples, spec, tau, dense_flops, n_layers):
+    """The CPU oracle on a bounded sample of the stack: for each sampled layer, batch element 0 and 4 of the
+    32 heads - score, select, compaction, kept-token attention (prefill) and one decode step (append + Eq. (5))
+    over the evicted cache of those heads; times scaled to all heads, batch elements and layers."""
+    import numpy as np
+    from oracle import zipvl_oracle as oz
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    t_prefill = t_decode = 0.0
+    r = np.random.Generator(np.random.PCG64(9))
+    for (li, Q, K, V, probe, scale) in samples:
+        hs = Q.shape[0]
+        t0 = time.perf_counter()
+        mass, rank = oz.token_scores(Q, K, probe, scale)
+        sel = [oz.select(mass[g].astype(np.float32), rank[g].astype(np.float32), tau) for g in range(hs)]
+        caches = [oz.compact_kv(K[g], V[g], sel[g][1]) for g in range(hs)]
+        for g in range(hs):
+            oz.kept_token_attention(Q[g], K[g], V[g], sel[g][1], scale)
+        t_prefill += time.perf_counter() - t0
+        q, kn, vn = (r.standard_normal((hs, spec.d)) for _ in range(3))
+        t0 = time.perf_counter()
+        for g in range(hs):
+            oz.decode_step(q[g], kn[g], vn[g], caches[g][0], caches[g][1], caches[g][2], scale)
+        t_decode += time.perf_counter() - t0
+    heads_sampled = sum(s[1].shape[0] for s in samples)
+    per_head_layer = t_prefill / heads_sampled
+    t_layer = per_head_layer * spec.Hq * spec.B
+    return {
+        "value": dense_flops / t_layer / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": int(threads), "kind": "oracle",
+        "sample": f"layers {[s[0] for s in samples]}, batch element 0, heads 0..{samples[0][1].shape[0] - 1}: score + select + compaction + "
+                  f"kept-token attention timed whole, scaled x{spec.Hq * spec.B / samples[0][1].shape[0]:.0f} to {spec.B} x {spec.Hq} heads per layer "
+                  "(extrapolated); decode: one oracle step (append + attention) on the same heads' evicted caches, scaled to "
+                  f"{spec.B * spec.Hq} units x {n_layers} layers",
+        "ms_per_layer_extrapolated": 1e3 * t_layer,
+        "decode_ms_per_step_extrapolated": 1e3 * t_decode / heads_sampled * spec.Hq * spec.B * n_layers,
+        "parts_s": {"prefill_sample": t_prefill, "decode_sample": t_decode},
+        "host_cpu_count": os.cpu_count(),
+    }
+
+
 def cpu_baseline(w, tau, dense_flops):
     """The CPU oracle as it stands, timed on a bounded sample of the same layer."""
     import numpy as np
@@ -110,7 +157,8 @@ def run_stack(args):
     lt = torch.empty((units,), dtype=torch.int32, device=dev)
     Kt4, Vt4 = Kt.view(B, H, n, d), Vt.view(B, H, n, d)
     ws_s = ws_p = None
-    caches, fulls, quants, kept, layer_ms = [], [], [], [], []
+    caches, fulls, quants, kept, layer_ms, samples = [], [], [], [], [], []
+    sample_layers = {0, (L - 1) // 2, L - 1}
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for layer in range(L):
         li = layer * (spec.layers - 1) // max(1, L - 1) if L < spec.layers else layer   # spread over the ramp
@@ -125,8 +173,11 @@ def run_stack(args):
             z.zipvl_select(mass, rank, tau, idx=idx, k=k)
             z.zipvl_compact_kv(K, V, idx, k, n, Kc=Kt, Vc=Vt, length=lt)
             z.zipvl_sparse_prefill(Q, Kt4, Vt4, idx, k, scale, z.OUT_FULL | z.KV_ALREADY_COMPACT, O=O, ws=ws_p)
-        one_layer()                                   # warm-up of this layer's shapes
+        for _ in range(max(1, args.warmup)):           # warm-up of this layer's shapes
+            one_layer()
         torch.cuda.synchronize()
+        if layer in sample_layers and not args.no_cpu_baseline:
+            samples.append((li, Q[0, :4].float().cpu().numpy(), K[0, :4].float().cpu().numpy(), V[0, :4].float().cpu().numpy(), probe, scale))
         ev0.record()
         for _ in range(args.steps):
             one_layer()
@@ -252,7 +303,7 @@ def run_stack(args):
     out = {
         "metric": "sparse-prefill dense-equivalent TFLOP/s (ms/layer in ms_per_step, tokens kept % in kept_pct)",
         "value": dense_flops / (ms_layer * 1e-3) / 1e12, "unit": "TFLOP/s (dense-equivalent)",
-        "n_gpus": 1, "steps": args.steps, "warmup": 1, "ms_per_step": ms_layer, "higher_is_better": True,
+        "n_gpus": 1, "steps": args.steps, "warmup": max(1, args.warmup), "ms_per_step": ms_layer, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic (seeded torch device generator)",
         "config": {"workload": spec.name, "layers": L, "B": B, "Hq": H, "Hkv": H, "n": n, "d": d, "tau": tau,
                    "decode_steps": steps_dec},
@@ -260,8 +311,12 @@ def run_stack(args):
         "layer_ms_first_last": [layer_ms[0], layer_ms[-1]],
         "decode": res, "decode_speedup_evicted_vs_full": res["full"]["ms_per_step"] / res["evicted"]["ms_per_step"],
         "roofline": {"kernel": "decode_step_kernel (evicted caches)", "bound": "hbm", "achieved": res["evicted"]["GBps"],
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["evicted"]["GBps"] / HBM_PEAK_GBS, "traffic": None,
-                     "note": "whole decode step (one fused launch per layer: append, split-KV attention, merge)"},
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["evicted"]["GBps"] / HBM_PEAK_GBS,
+                     "traffic": read_traffic("decode_step_kernel", spec.name + "-evicted"), "traffic_source": TRAFFIC_NOTE,
+                     "bytes_per_launch": res["evicted"]["GB_read_per_step"] * 1e9 / L,
+                     "avg_launch_us": 1e3 * res["evicted"]["ms_per_step"] / L,
+                     "note": "whole decode step (one fused launch per layer: append, split-KV attention, merge); achieved = algorithmic "
+                             "bytes of a step (2 x cached rows x d x 2 B over all layers) / step time; per launch: both divided by the layer count"},
         "paper_context": "paper reports 2.8x decode throughput at 16K tokens on one A100 (larger batch fits after eviction)",
     }
     if not args.no_peaks:
@@ -269,6 +324,8 @@ def run_stack(args):
         out["measured_peaks"] = {"mfma_bf16_TFLOPs": tf, "read_GBps": gb,
                                  "note": "sustained by this GPU in the library's probe kernels (independent MFMA chains; one 4 GiB read)"}
         out["roofline"]["frac_of_measured_peak"] = res["evicted"]["GBps"] / gb
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_stack(samples, spec, tau, dense_flops, L)
     print(json.dumps(out))
 
 
@@ -307,6 +364,8 @@ def main():
     if args.workload == 5:
         if args.steps == 50:
             args.steps = 3
+        if args.warmup == 10:
+            args.warmup = 2
         return run_stack(args)
 
     import numpy as np
@@ -455,7 +514,7 @@ def main():
     achieved = kept_flops / (flash_us * 1e-6) / 1e12
     roofline = {"kernel": "flash_kept_kernel", "bound": "mfma", "achieved": achieved, "peak": peak,
                 "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": read_traffic("flash_kept_kernel", spec.name),
+                "traffic": read_traffic("flash_kept_kernel", spec.name), "traffic_source": TRAFFIC_NOTE,
                 "flops_per_launch": kept_flops, "avg_launch_us": flash_us}
     e = 2 if spec.dtype == "bf16" else 4
     hbm = {}

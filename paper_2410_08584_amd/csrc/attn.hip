@@ -33,6 +33,7 @@
 #include <atomic>
 
 #include "launch.h"
+#include "ldsload.h"
 
 namespace zipvl {
 
@@ -121,44 +122,9 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
 }
 
 // ------------------------------------------------------------------ flash
-// byte offset of logical 16-byte chunk `c` in a swizzled LDS row (sw = row & 7)
-__device__ __forceinline__ int swz_chunk(int c, int sw) { return (c ^ sw) << 4; }
-
 // One tile (TILE_BYTES contiguous in global memory) -> one LDS buffer, without passing through
 // registers: every wave issues NLD loads of 1 KiB, lane L of a load writes LDS bytes [16 L, 16 L + 16)
 // of that KiB, and picks the global chunk that belongs there under the row swizzle.
-// (M0 is named as clobbered on purpose: the instruction reads its LDS base from it and nothing else here uses M0.)
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-// One 1-KiB direct-to-LDS load of the wave: lane L's 16 bytes at gbase + goff land at LDS byte
-// lds_base + 16 L (gbase and lds_base wave-uniform, goff a per-lane byte offset below 4 GiB).
-// global_load_lds_dwordx4 takes the LDS base from M0.  The instruction is written out rather than
-// taken from the builtin because the compiler, while such a load is pending, turns every LDS-read
-// wait into a wait for ALL outstanding LDS reads, which stalls the matrix pipeline on each operand
-// fetch; completion is awaited explicitly (vmcnt) at the end of every pipeline step instead.
-__device__ __forceinline__ void load_kib_to_lds(const char* gbase, int goff, unsigned lds_base) {
-    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(m0v), "v"(goff), "s"(gbase) : "memory", "m0");
-}
-
-// The same load, placed by data flow instead of by program order: it is tied to a register (`pin`, passed
-// through unchanged) so that it issues after the instruction that produced `pin` and before the one that
-// consumes it, without ordering the surrounding LDS reads the way a statement with side effects would.
-// Used to spread a step's loads between its matrix instructions; the buffers written are not read before
-// the barrier that ends the step, and that barrier is preceded by a wait for all of the wave's loads.
-__device__ __forceinline__ void load_kib_to_lds_pinned(const char* gbase, int goff, unsigned lds_base, unsigned& pin) {
-    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);
-    asm("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
-        : "+v"(pin) : "s"(m0v), "v"(goff), "s"(gbase) : "m0");
-}
-
-#pragma clang diagnostic pop
-
-__device__ __forceinline__ unsigned lds_address(const char* p) {
-    return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
-}
-
 template <int NW, int NLD>
 __device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w, const int (&off)[NLD]) {
     const unsigned lbase = lds_address(lbuf);

@@ -1,361 +1,365 @@
 // Probe-token importance scores (supplementary Eq. (A); Eq. (6), Eq. (8);
 // Algorithm 1 steps 2-4).  The m x n probe attention matrix is never stored:
 //   pass 1  row statistics: for each (head, probe row) the maximum and the
-//           exp-sum of the masked, scaled logits over a slice of 128 keys;
-//           a small kernel merges the slices into one exponent offset per row;
-//   pass 2  the logits are recomputed, normalised with that offset, summed
-//           down the probe rows and over the query heads of the group, and
-//           written as mass / rank.
-// Both passes share one kernel body.  A workgroup (4 waves) owns 128 keys of
-// one KV head: each wave keeps the fragments of its 32 keys in registers and
-// walks over the group's query heads, whose probe rows pass through LDS a few
-// heads at a time (small footprint, several workgroups per CU), so K is read
-// from memory once per pass.  A 32-key x 32-probe tile is one 32x32 MFMA
-// accumulator.  Pass 1 computes K Q^T (lane = probe column: row statistics
-// stay in the lane); pass 2 computes Q K^T (lane = key column: column sums
-// stay in the lane).  Same fragments, operands swapped.
+//           exp-sum of the masked, scaled logits over the chunk of keys a
+//           workgroup owns (one partial pair per row and chunk);
+//   pass 2  merges the partial pairs of its rows into one exponent offset per
+//           row (in its prologue: no launch in between), recomputes the
+//           logits, normalises them with that offset, sums them down the probe
+//           rows and over the query heads of the group, and writes mass / rank.
+// Both passes share one kernel body.  A workgroup owns a chunk of keys of one
+// KV head and streams it through LDS in stages of 32 KiB, loaded straight from
+// global memory (no staging registers), double buffered.  The work of a stage
+// is a grid of 32-key x 32-probe tiles, one 32x32 MFMA accumulator each.  A
+// wave owns one (query head, block of 32 probe rows) - its "task" - for the
+// whole kernel: the probe rows' fragments stay in its registers, and the key
+// fragments of a tile come from LDS.  With few tasks (one query head per KV
+// head) several waves share a task and split the key blocks of a stage; with
+// more tasks than waves the chunk is streamed once per round of tasks.
+// Pass 1 computes K Q^T (lane = probe column: row statistics stay in the
+// lane); pass 2 computes Q K^T (lane = key column: column sums stay in the
+// lane, the tasks' sums of a stage meet in LDS and are added in task order, so
+// the result does not depend on scheduling).
+#include <algorithm>
 #include <atomic>
 
 #include "launch.h"
+#include "ldsload.h"
 
 namespace zipvl {
 
-// Probe rows are handled in blocks of 32 (NB = 2 for m <= 64, NB = 4 for m <= 128; rows beyond m are masked out).
-constexpr int kMaxNB = ZIPVL_MAX_PROBES / 32;
 constexpr int kMaxGroup = 16;
-constexpr int kScoreWaves = 4;
-constexpr int kScoreThreads = 64 * kScoreWaves;
-constexpr int kScoreKeys = 32 * kScoreWaves;  // keys per workgroup
-
-template <typename T, int D, int NB = 2>
-struct ScoreCfg {
-    static constexpr int kProbes = NB * 32;
-    static constexpr int E = Elem<T>::kBytes;
-    static constexpr int CH = D / Elem<T>::kPerChunk;      // fragments per row per lane
-    static constexpr int QS = D * E + 16;                   // padded LDS row of a probe query (bytes)
-    static constexpr int HEAD_BYTES = kProbes * QS;
-    static constexpr int GC = (36 * 1024) / HEAD_BYTES > 0 ? (36 * 1024) / HEAD_BYTES : 1;   // heads staged in LDS at once
-    static constexpr int CPR = D * E / 16;                  // 16-byte chunks per row
-};
+constexpr int kStageBytes = 32 * 1024;      // keys staged in LDS at once: 32 KiB / row bytes
 
 template <typename T, int D>
-__device__ __forceinline__ void load_row_frags(const T* row, int h, uintx4 (&f)[ScoreCfg<T, D>::CH]) {
-#pragma unroll
-    for (int c = 0; c < ScoreCfg<T, D>::CH; ++c)
-        f[c] = load16(row + c * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
+struct ScoreCfg {
+    static constexpr int E = Elem<T>::kBytes;
+    static constexpr int CH = D / Elem<T>::kPerChunk;      // fragments per row per lane
+    static constexpr int RB = D * E;                        // bytes per key row
+    static constexpr int SK = kStageBytes / RB;             // keys per stage
+    static constexpr int KBS = SK / 32;                     // 32-key blocks per stage
+};
+
+// The statistics (maximum m, exp-sum l relative to m, log2 domain scale c) of two disjoint key sets of one row.
+__device__ __forceinline__ void merge_stats(float& m, float& l, float m2, float l2, float c) {
+    const float M = fmaxf(m, m2);
+    if (M > -INFINITY) l = l * fast_exp2((m - M) * c) + l2 * fast_exp2((m2 - M) * c);
+    m = M;
 }
 
-// PASS 1: partial[(bh * nsplit + split) * 64 + probe] = (raw-logit maximum, sum of exp2((s - max) * c))
-// PASS 2: mass / rank of the workgroup's keys, from bias[bh * 64 + probe] = max * c + log2(sum)
-// GCT = query heads whose probe rows are staged in LDS at once (1 when the group has a single head: fewer
-// staging registers and a smaller LDS footprint, so more workgroups per CU hide the load latency)
-// bf16: at least three workgroups per CU; the register budget that follows keeps the accumulators in architectural VGPRs,
-// where the vector ALU reads them without copies.
-template <typename T, int D, int PASS, int NB, int GCT>
-__global__ __launch_bounds__(kScoreThreads, (Elem<T>::kBytes == 2 ? 3 : 1)) void score_pass_kernel(
+// PASS 1: partial[((b*Hq + head) * nsplit + chunk) * np + probe] = (raw-logit maximum, sum of exp2((s - max) * c))
+// PASS 2: mass / rank of the workgroup's keys; nsplit = chunks of pass 1
+// np = probe rows rounded up to a multiple of 32 (NB blocks); rows beyond m are masked out.
+// bpc = 32-key blocks per chunk of this pass.
+template <typename T, int D, int PASS, int NWV>
+__global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV == 8) ? 2 : 4) void score_kernel(
     const T* __restrict__ Q, const T* __restrict__ K,
     int64_t qs0, int64_t qs1, int64_t qs2, int64_t ks0, int64_t ks1, int64_t ks2,
-    ProbeList probes, int m, int n, int n_eff, float c, float2* __restrict__ partial, int nsplit,
-    const float* __restrict__ bias, float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv)
+    ProbeList probes, int m, int NB, int n, int n_eff, float c, float2* __restrict__ partial, int nsplit, int bpc,
+    float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv)
 {
-    using C = ScoreCfg<T, D, NB>;
-    constexpr int CH = C::CH;
-    constexpr int kProbes = NB * 32, kNB = NB;
-    extern __shared__ __attribute__((aligned(16))) char smem[];     // [gc][64] padded probe rows
-    __shared__ int sp[kProbes];
-    __shared__ __attribute__((aligned(16))) float row_bias[kMaxGroup][kProbes];
-    const int G = Hq / Hkv;
-    const int u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 31, h = lane >> 5;
-    const int block_begin = blockIdx.x * kScoreKeys;
+    using C = ScoreCfg<T, D>;
+    constexpr int CH = C::CH, RB = C::RB, SK = C::SK, KBS = C::KBS;
+    constexpr int NLD = kStageBytes / 1024 / NWV;                    // 1-KiB loads per wave per stage
+    constexpr int kThreads = 64 * NWV;
+    extern __shared__ __attribute__((aligned(16))) char kstage[];   // two stage buffers
+    __shared__ int sp[ZIPVL_MAX_PROBES];
+    __shared__ float2 wstat[PASS == 1 ? NWV : 1][32];                // pass 1: per-wave row statistics
+    __shared__ __attribute__((aligned(16))) float row_bias[PASS == 2 ? NWV : 1][32];
+    __shared__ float colbuf[PASS == 2 ? 2 : 1][PASS == 2 ? NWV : 1][PASS == 2 ? SK : 1];
 
-    if (PASS == 2 && block_begin >= n_eff) {          // no probe row sees these keys
-        for (int j = block_begin + tid; j < min(n, block_begin + kScoreKeys); j += kScoreThreads) {
-            mass[(int64_t)u * n + j] = 0.f;
-            if (rank) rank[(int64_t)u * n + j] = 0.f;
-        }
-        return;
-    }
-    if (tid < kProbes) sp[tid] = probes.pos[tid];          // -1 beyond m
-    if (PASS == 2)
-        for (int t = tid; t < G * kProbes; t += kScoreThreads)
-            (&row_bias[0][0])[t] = bias[(int64_t)(b * Hq + g * G) * kProbes + t];
+    const int G = Hq / Hkv, np = NB * 32, NT = G * NB;
+    const int u = blockIdx.y, b = u / Hkv, g = u - b * Hkv;
+    const int tid = threadIdx.x, lane = tid & 63, i = lane & 31, h = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave-uniform: everything derived from it lives in scalar registers
+    const int nblk = ((PASS == 1 ? n_eff : n) + 31) >> 5;
+    const int blk0 = blockIdx.x * bpc, blk1 = min(blk0 + bpc, nblk);
+    if (blk0 >= blk1) return;
+    const int S = (blk1 - blk0 + KBS - 1) / KBS;                     // stages of this chunk
+
+    if (tid < ZIPVL_MAX_PROBES) sp[tid] = probes.pos[tid];           // -1 beyond m
     __syncthreads();
     const int Pmin = sp[0];
-    const bool has_pad = m < kProbes;
+    const bool has_pad = m < np;
 
-    // this wave's 32 keys stay in registers for every head of the group
-    const int jb = block_begin + w * 32;
-    const bool live = jb < n_eff;                           // wave-uniform
-    uintx4 kf[CH];
-    load_row_frags<T, D>(K + b * ks0 + g * ks1 + (int64_t)min(jb + i, n - 1) * ks2, h, kf);
-    const bool masked = has_pad || jb + 31 > Pmin;          // wave-uniform
+    // waves -> tasks.  Fewer tasks than waves: KS waves share a task and take the key blocks slot, slot + KS, ...
+    const bool few = NT < NWV;
+    const int KS = few ? NWV / NT : 1;
+    const int rounds = few ? 1 : (NT + NWV - 1) / NWV;
+    const int ts = few ? w % NT : w;                                 // task slot inside a round
+    const int slot = few ? w / NT : 0;
 
-    float colsum = 0.f;                                     // PASS 2
-    float2* wstat = reinterpret_cast<float2*>(smem + GCT * C::HEAD_BYTES);   // PASS 1: [wave][head of chunk][nb][lane]
-
-    // Probe rows travel global -> registers -> LDS one chunk of GC heads at a time; the next chunk
-    // is requested before the current one is consumed, so its latency hides under the matrix work.
-    constexpr int NPRE = GCT * kProbes * C::CPR / kScoreThreads;
-    static_assert(NPRE * kScoreThreads == GCT * kProbes * C::CPR, "chunk must divide evenly over the threads");
-    uintx4 pre[NPRE];
-    // where this thread's NPRE chunks sit inside a chunk of heads: fixed for the whole kernel
-    int pre_head[NPRE];
-    int64_t pre_off[NPRE];
+    // where this lane's NLD 16-byte pieces of a stage come from: row inside the stage and chunk under the row swizzle
+    const char* Ku = reinterpret_cast<const char*>(K + b * ks0 + g * ks1);
+    const int row_stride = (int)ks2 * C::E;                          // bytes; a stage spans less than 2 GiB (checked on the host)
+    const unsigned lds0 = lds_address(kstage);
+    // where this lane's NLD 16-byte pieces of a stage come from: byte offset of (row inside the stage, chunk under the row swizzle)
+    int ld_off[NLD];
 #pragma unroll
-    for (int q = 0; q < NPRE; ++q) {
-        const int t = tid + q * kScoreThreads;
-        const int row = t / C::CPR, cc = t - row * C::CPR;
-        pre_head[q] = row / kProbes;
-        pre_off[q] = (int64_t)sp[min(row - pre_head[q] * kProbes, m - 1)] * qs2 + cc * Elem<T>::kPerFrag;
+    for (int q = 0; q < NLD; ++q) {
+        const int o = (q * NWV + w) * 1024 + lane * 16;              // LDS byte of the piece: row r, position p of the row
+        const int r = o / RB, p = (o % RB) >> 4;
+        ld_off[q] = r * row_stride + ((p ^ (r & 7)) << 4);
     }
-    auto fetch_chunk = [&](int h0) {
-        const T* base = Q + b * qs0 + (int64_t)(g * G + h0) * qs1;
-        const int last = min(GCT, G - h0) - 1;               // heads beyond the chunk re-read its last head
+    auto issue_stage = [&](int s, int buf) {
+        const int row0 = (blk0 + s * KBS) * 32;
+        const int rows = min(blk1 * 32 - row0, SK);                  // rows of this stage that belong to the chunk
+        const char* gbase = Ku + (int64_t)row0 * row_stride;
+        const int lim = n - 1 - row0;                                // rows past the last key re-read the stage's first row (masked later)
 #pragma unroll
-        for (int q = 0; q < NPRE; ++q) pre[q] = load16(base + min(pre_head[q], last) * qs1 + pre_off[q]);
-    };
-    fetch_chunk(0);
-    for (int h0 = 0; h0 < G; h0 += GCT) {
-        const int gc = min(GCT, G - h0);
-        if (h0) __syncthreads();                            // previous chunk fully consumed
-#pragma unroll
-        for (int q = 0; q < NPRE; ++q) {
-            const int t = tid + q * kScoreThreads;
-            const int row = t / C::CPR, cc = t - row * C::CPR;
-            store16(smem + row * C::QS + cc * 16, pre[q]);  // rows beyond gc heads hold duplicates, never read
+        for (int q = 0; q < NLD; ++q) {
+            const int r = ((q * NWV + w) * 1024 + lane * 16) / RB;
+            if (((q * NWV + w) * 1024) / RB < rows)                  // wave-uniform
+                load_kib_to_lds(gbase, r <= lim ? ld_off[q] : 0, lds0 + buf * kStageBytes + (q * NWV + w) * 1024);
         }
-        __syncthreads();
-        if (h0 + GCT < G) fetch_chunk(h0 + GCT);
+    };
+
 #pragma unroll 1
-        for (int hh = 0; hh < gc; ++hh) {
-            const char* qh = smem + hh * C::HEAD_BYTES;
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int task = rd * NWV + ts;
+        const bool active = few ? w < NT * KS : task < NT;
+        const int ntr = few ? NT : min(NWV, NT - rd * NWV);          // tasks of this round
+        const int head = active ? task / NB : 0, nb = active ? task - (task / NB) * NB : 0;
+        const int bh = b * Hq + g * G + head;
+
+        if (rd) __syncthreads();                                     // the stage buffers of the previous round are free
+        issue_stage(0, 0);
+        if (S > 1) issue_stage(1, 1);
+
+        // this wave's probe rows: fragments of row nb*32 + i, held for the whole round
+        uintx4 qf[CH];
+        {
+            const int prow = sp[min(nb * 32 + i, m - 1)];
+            const T* qp = Q + b * qs0 + (int64_t)(g * G + head) * qs1 + (int64_t)prow * qs2 + h * Elem<T>::kPerFrag;
 #pragma unroll
-            for (int nb = 0; nb < kNB; ++nb) {
-                float2 stat = make_float2(-INFINITY, 0.f);
-                if (live) {
-                    uintx4 qf[CH];
+            for (int cc = 0; cc < CH; ++cc) qf[cc] = load16(qp + cc * Elem<T>::kPerChunk);
+        }
+        const int Pm = sp[nb * 32 + i];                              // PASS 1: position of this lane's probe (-1: padding)
+
+        if (PASS == 2) {
+            // merge the chunk statistics of this task's 32 rows: lane = (row, half of the chunks)
+            float M = -INFINITY, L = 0.f;
+            const float2* p = partial + (int64_t)bh * nsplit * np + nb * 32;     // wave-uniform base; the rest fits 32 bits (host check)
+            for (int s0 = h; s0 < nsplit; s0 += 16) {                // 8 independent loads per lane and round
+                float2 v[8];
 #pragma unroll
-                    for (int cc = 0; cc < CH; ++cc)
-                        qf[cc] = *reinterpret_cast<const uintx4*>(qh + (nb * 32 + i) * C::QS + cc * 32 + h * 16);
+                for (int q = 0; q < 8; ++q) {
+                    const int s = s0 + 2 * q;
+                    v[q] = s < nsplit ? p[s * np + i] : make_float2(-INFINITY, 0.f);
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) merge_stats(M, L, v[q].x, v[q].y, c);
+            }
+            merge_stats(M, L, __shfl_xor(M, 32), __shfl_xor(L, 32), c);
+            if (active && slot == 0 && h == 0)
+                row_bias[ts][i] = (nb * 32 + i < m && L > 0.f) ? M * c + __log2f(L) : INFINITY;
+            __syncthreads();
+        }
+
+        float m_run = -INFINITY, l_run = 0.f;                        // PASS 1
+        __builtin_amdgcn_s_waitcnt(0);                               // this wave's pieces of stages 0 and 1 have landed
+        __syncthreads();
+#pragma unroll 1
+        for (int s = 0; s < S; ++s) {
+            const int buf = s & 1;
+            const char* kb0 = kstage + buf * kStageBytes;
+            const int sblk = blk0 + s * KBS;                         // first key block of the stage
+            if (active) {
+#pragma unroll 1
+                for (int kb = slot; kb < KBS && sblk + kb < blk1; kb += KS) {
+                    const int jb = (sblk + kb) * 32;
+                    if (PASS == 2 && jb >= n_eff) {                  // no probe row sees these keys
+                        if (h == 0) colbuf[buf][ts][kb * 32 + i] = 0.f;
+                        continue;
+                    }
+                    const char* krow = kb0 + (kb * 32 + i) * RB;
+                    auto kfrag = [&](int cc) { return *reinterpret_cast<const uintx4*>(krow + swz_chunk(2 * cc + h, i & 7)); };
                     floatx16 acc = {0};
+                    const bool masked = has_pad || jb + 31 > Pmin;  // wave-uniform
                     if (PASS == 1) {
 #pragma unroll
-                        for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(kf[cc], qf[cc], acc);
+                        for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(kfrag(cc), qf[cc], acc);
                         // acc[r]: key jb + acc_row(r, h), probe column nb*32 + i  (raw logit)
                         float sv[16], mx = -INFINITY;
 #pragma unroll
                         for (int r = 0; r < 16; ++r) sv[r] = acc[r];
                         if (masked) {
-                            const int Pm = sp[nb * 32 + i];
 #pragma unroll
                             for (int r = 0; r < 16; ++r)
                                 if (jb + acc_row(r, h) > Pm) sv[r] = -INFINITY;
                         }
 #pragma unroll
                         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sv[r]);
-                        float sum = 0.f;
-                        if (mx > -INFINITY) {               // statistics of this lane's 16 keys only
-                            const float mc = mx * c;
+                        const float m_new = fmaxf(m_run, mx);
+                        if (m_new > -INFINITY) {
+                            const float mc = m_new * c;
+                            float sum = l_run * fast_exp2(m_run * c - mc);      // 0 while m_run = -inf
 #pragma unroll
                             for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(sv[r], c, -mc));
+                            l_run = sum;
+                            m_run = m_new;
                         }
-                        stat = make_float2(mx, sum);
                     } else {
 #pragma unroll
-                        for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(qf[cc], kf[cc], acc);
-                        // acc[r]: probe row nb*32 + acc_row(r, h), key column jb + i
+                        for (int cc = 0; cc < CH; ++cc) acc = mma_frag<T>(qf[cc], kfrag(cc), acc);
+                        // acc[r]: probe row nb*32 + acc_row(r, h), key column jb + i; rb[r]: exponent offset of that row
                         float rb[16];
 #pragma unroll
                         for (int a = 0; a < 4; ++a) {
-                            const floatx4 v = *reinterpret_cast<const floatx4*>(&row_bias[h0 + hh][nb * 32 + 8 * a + 4 * h]);
+                            const floatx4 v = *reinterpret_cast<const floatx4*>(&row_bias[ts][8 * a + 4 * h]);
                             rb[4 * a] = v[0]; rb[4 * a + 1] = v[1]; rb[4 * a + 2] = v[2]; rb[4 * a + 3] = v[3];
                         }
                         float sum = 0.f;
                         if (masked) {
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
-                                const float p = fast_exp2(fmaf(acc[r], c, -rb[r]));
-                                sum += jb + i > sp[nb * 32 + acc_row(r, h)] ? 0.f : p;
+                                const float pr = fast_exp2(fmaf(acc[r], c, -rb[r]));
+                                sum += jb + i > sp[nb * 32 + acc_row(r, h)] ? 0.f : pr;
                             }
                         } else {
 #pragma unroll
                             for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(acc[r], c, -rb[r]));
                         }
-                        colsum += sum;
+                        sum += __shfl_xor(sum, 32);
+                        if (h == 0) colbuf[buf][ts][kb * 32 + i] = sum;
                     }
                 }
-                if (PASS == 1) wstat[((w * GCT + hh) * kNB + nb) * 64 + lane] = stat;
             }
-        }
-        if (PASS == 1) {
-            // merge the 4 waves x 2 half-waves that saw each (head, probe row) and emit the slice partial
-            __syncthreads();
-            for (int t = tid; t < gc * kProbes; t += kScoreThreads) {
-                const int hh = t / kProbes, pc = t - hh * kProbes, nb = pc >> 5, ii = pc & 31;
-                float M = -INFINITY;
-#pragma unroll
-                for (int ww = 0; ww < kScoreWaves; ++ww)
-#pragma unroll
-                    for (int hf = 0; hf < 2; ++hf)
-                        M = fmaxf(M, wstat[((ww * GCT + hh) * kNB + nb) * 64 + hf * 32 + ii].x);
-                float L = 0.f;
-                if (M > -INFINITY) {
-#pragma unroll
-                    for (int ww = 0; ww < kScoreWaves; ++ww)
-#pragma unroll
-                        for (int hf = 0; hf < 2; ++hf) {
-                            const float2 v = wstat[((ww * GCT + hh) * kNB + nb) * 64 + hf * 32 + ii];
-                            L += v.y * fast_exp2((v.x - M) * c);
-                        }
+            __builtin_amdgcn_s_waitcnt(0);                           // this wave's pieces of stage s + 1 have landed
+            __syncthreads();                                         // stage s is consumed, its column sums are in LDS
+            if (s + 2 < S) issue_stage(s + 2, buf);
+            if (PASS == 2) {
+                // add the tasks' sums of stage s in task order and write the scores of its keys
+                const int row0 = sblk * 32;
+                const int keys = min(min(blk1 * 32, n) - row0, SK);
+                for (int t = tid; t < keys; t += kThreads) {
+                    const int j = row0 + t;
+                    float a = (rd && j < n_eff) ? mass[(int64_t)u * n + j] : 0.f;     // tasks of earlier rounds
+                    if (j < n_eff)
+                        for (int q = 0; q < ntr; ++q) a += colbuf[buf][q][t];
+                    if (rd + 1 < rounds) {
+                        mass[(int64_t)u * n + j] = a;
+                    } else {
+                        a /= (float)G;
+                        int cnt = 0;
+                        if (j <= Pmin) cnt = m;
+                        else for (int q = 0; q < m; ++q) cnt += sp[q] >= j ? 1 : 0;
+                        mass[(int64_t)u * n + j] = a / (float)m;
+                        if (rank) rank[(int64_t)u * n + j] = cnt > 0 ? a / (float)cnt : 0.f;
+                    }
                 }
-                partial[((int64_t)(b * Hq + g * G + h0 + hh) * nsplit + blockIdx.x) * kProbes + pc] = make_float2(M, L);
             }
         }
-    }
 
-    if (PASS == 2) {
-        const float a = (colsum + __shfl_xor(colsum, 32)) / (float)G;
-        const int j = jb + i;
-        if (h == 0 && j < n) {
-            int cnt = 0;
-            if (j <= Pmin) cnt = m;
-            else for (int t = 0; t < m; ++t) cnt += sp[t] >= j ? 1 : 0;
-            mass[(int64_t)u * n + j] = a / (float)m;
-            if (rank) rank[(int64_t)u * n + j] = cnt > 0 ? a / (float)cnt : 0.f;
+        if (PASS == 1) {
+            // the two half-waves saw different keys of the same rows; waves that share a task saw different key blocks
+            merge_stats(m_run, l_run, __shfl_xor(m_run, 32), __shfl_xor(l_run, 32), c);
+            if (h == 0) wstat[w][i] = active ? make_float2(m_run, l_run) : make_float2(-INFINITY, 0.f);
+            __syncthreads();
+            for (int t = tid; t < ntr * 32; t += kThreads) {
+                const int q = t >> 5, pc = t & 31;                   // task slot, probe row of its block
+                float M = -INFINITY, L = 0.f;
+                for (int sl = 0; sl < KS; ++sl) {
+                    const float2 v = wstat[few ? sl * NT + q : q][pc];
+                    merge_stats(M, L, v.x, v.y, c);
+                }
+                const int tk = rd * NWV + q, hd = tk / NB, nbk = tk - hd * NB;
+                partial[((int64_t)(b * Hq + g * G + hd) * nsplit + blockIdx.x) * np + nbk * 32 + pc] = make_float2(M, L);
+            }
         }
-    }
-}
-
-// Merge the per-slice statistics of every (head, probe row) into one exponent offset
-// bias = max * c + log2(sum), so that exp2(s * c - bias) is the normalised probability.
-// Block = np probe rows x 8 slice groups.
-__global__ __launch_bounds__(1024) void score_rowfinal_kernel(
-    const float2* __restrict__ partial, int nsplit, int m, int np, float c, float* __restrict__ bias)
-{
-    __shared__ float2 red[8][ZIPVL_MAX_PROBES];
-    const int bh = blockIdx.x, pc = threadIdx.x % np, sg = threadIdx.x / np;
-    const float2* p = partial + (int64_t)bh * nsplit * np + pc;
-    float M = -INFINITY, L = 0.f;
-    for (int s0 = sg; s0 < nsplit; s0 += 32) {              // 4 independent loads per round
-        float2 v[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int s = s0 + 8 * q;
-            v[q] = s < nsplit ? p[(int64_t)s * np] : make_float2(-INFINITY, 0.f);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const float Mn = fmaxf(M, v[q].x);
-            if (Mn > -INFINITY) L = L * fast_exp2((M - Mn) * c) + v[q].y * fast_exp2((v[q].x - Mn) * c);
-            M = Mn;
-        }
-    }
-    red[sg][pc] = make_float2(M, L);
-    __syncthreads();
-    if (sg == 0) {
-        float Mt = -INFINITY;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) Mt = fmaxf(Mt, red[q][pc].x);
-        float Lt = 0.f;
-        if (Mt > -INFINITY) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) Lt += red[q][pc].y * fast_exp2((red[q][pc].x - Mt) * c);
-        }
-        bias[(int64_t)bh * np + pc] = (pc < m && Lt > 0.f) ? Mt * c + __log2f(Lt) : INFINITY;
     }
 }
 
 // ---------------------------------------------------------------- host side
-static int score_splits(const zipvl_dims& d) { return (d.n + kScoreKeys - 1) / kScoreKeys; }
-static int probe_rows(int m) { return m <= 64 ? 64 : 128; }
+static int probe_rows(int m) { return (m + 31) / 32 * 32; }
 
-static size_t score_partial_bytes(const zipvl_dims& d, int m) {
-    return (size_t)d.B * d.Hq * score_splits(d) * probe_rows(m) * sizeof(float2);
+// Workgroups that fit the chip at once with `waves` waves each (registers allow 16 waves per CU here).
+static int resident_slots(int waves) {
+    static std::atomic<int> cus{0};
+    int c = cus.load();
+    if (!c) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
+        cus = c = v;
+    }
+    return c * (16 / waves);
+}
+
+// 32-key blocks per chunk so that about `slots` workgroups cover `units` x nblk blocks
+static int blocks_per_chunk(int nblk, int units, int slots) {
+    const int chunks = std::max(1, std::min(nblk, slots / units));
+    return (nblk + chunks - 1) / chunks;
 }
 
 size_t score_workspace_bytes(const zipvl_dims& d, int m) {
-    return score_partial_bytes(d, m) + (size_t)d.B * d.Hq * probe_rows(m) * sizeof(float);
+    // one (max, sum) pair per head, probe row and pass-1 chunk; chunks per unit never exceed the resident slots
+    const int max_chunks = std::max(1, resident_slots(8) / std::max(1, d.B * d.Hkv));
+    return (size_t)d.B * d.Hq * max_chunks * probe_rows(m) * sizeof(float2);
 }
 
-template <typename T, int D, int NB, int GCT>
-static int launch_score_g(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
+template <typename T, int D, int NWV>
+static int launch_score_w(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
                           int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
 {
-    using C = ScoreCfg<T, D, NB>;
+    using C = ScoreCfg<T, D>;
     const float c = scale * kLog2e;
     float2* partial = (float2*)ws;
-    float* bias = (float*)((char*)ws + score_partial_bytes(d, m));
-    const int units = d.B * d.Hkv;
-    // probe rows of GC heads, then the per-wave statistics of pass 1
-    const size_t lds = (size_t)GCT * C::HEAD_BYTES + (size_t)kScoreWaves * GCT * NB * 64 * sizeof(float2);
+    const int units = d.B * d.Hkv, NB = probe_rows(m) / 32;
+    const size_t lds = 2 * kStageBytes;
     static std::atomic<bool> attr_done{false};
     if (!attr_done) {
-        const int cap = 96 * 1024;
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 1, NB, GCT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(&score_pass_kernel<T, D, 2, NB, GCT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, cap) != hipSuccess)
-            return set_error(ZIPVL_EHIP, "score: cannot reserve LDS for the probe rows");
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, D, 1, NWV>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, D, 2, NWV>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return set_error(ZIPVL_EHIP, "score: cannot reserve LDS for the key stages");
         attr_done = true;
     }
-    const int nsplit = (n_eff + kScoreKeys - 1) / kScoreKeys;
+    const int slots = resident_slots(NWV);
+    const int nblk1 = (n_eff + 31) / 32, bpc1 = blocks_per_chunk(nblk1, units, slots), nsplit = (nblk1 + bpc1 - 1) / bpc1;
+    const int nblk2 = (d.n + 31) / 32, bpc2 = blocks_per_chunk(nblk2, units, slots), chunks2 = (nblk2 + bpc2 - 1) / bpc2;
+    (void)C::SK;
     {
         KernelTimer tm(ZIPVL_K_SCORE_ROWSTATS, st);
-        hipLaunchKernelGGL((score_pass_kernel<T, D, 1, NB, GCT>), dim3(nsplit, units), dim3(kScoreThreads), lds, st,
+        hipLaunchKernelGGL((score_kernel<T, D, 1, NWV>), dim3(nsplit, units), dim3(64 * NWV), lds, st,
             (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-            d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, partial, nsplit,
-            (const float*)nullptr, (float*)nullptr, (float*)nullptr, d.Hq, d.Hkv);
+            d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, NB, d.n, n_eff, c, partial, nsplit, bpc1,
+            (float*)nullptr, (float*)nullptr, d.Hq, d.Hkv);
     }
     int rc = check_launch("score_rowstats");
     if (rc) return rc;
-    {
-        KernelTimer tm(ZIPVL_K_SCORE_ROWFINAL, st);
-        hipLaunchKernelGGL(score_rowfinal_kernel, dim3(d.B * d.Hq), dim3(NB * 32 * 8), 0, st,
-            (const float2*)partial, nsplit, m, NB * 32, c, bias);
-    }
-    rc = check_launch("score_rowfinal");
-    if (rc) return rc;
     KernelTimer tm(ZIPVL_K_SCORE_COLSUM, st);
-    hipLaunchKernelGGL((score_pass_kernel<T, D, 2, NB, GCT>), dim3(score_splits(d), units), dim3(kScoreThreads), lds, st,
+    hipLaunchKernelGGL((score_kernel<T, D, 2, NWV>), dim3(chunks2, units), dim3(64 * NWV), lds, st,
         (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
-        d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, d.n, n_eff, c, (float2*)nullptr, nsplit,
-        (const float*)bias, mass, rank, d.Hq, d.Hkv);
+        d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, NB, d.n, n_eff, c, partial, nsplit, bpc2,
+        mass, rank, d.Hq, d.Hkv);
     return check_launch("score_colsum");
 }
 
-template <typename T, int D, int NB>
+template <typename T, int D>
 static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
                           int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
 {
-    constexpr int GC = ScoreCfg<T, D, NB>::GC;
-    if constexpr (GC > 1) {
-        if (d.Hq == d.Hkv) return launch_score_g<T, D, NB, 1>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-    }
-    return launch_score_g<T, D, NB, GC>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-}
-
-template <typename T, int D>
-static int launch_score_nb(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
-                           int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
-{
-    if (m <= 64) return launch_score_t<T, D, 2>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-    return launch_score_t<T, D, 4>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    const int NT = (d.Hq / d.Hkv) * (probe_rows(m) / 32);            // (head, probe block) tasks per KV head
+    if (NT > 8) return launch_score_w<T, D, 16>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    return launch_score_w<T, D, 8>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
 }
 
 int launch_score(const void* Q, const void* K, const zipvl_dims& d, const int32_t* probe_pos, int m,
                  float scale, float* mass, float* rank, void* ws, hipStream_t st)
 {
     if (d.Hq / d.Hkv > kMaxGroup) return set_error(ZIPVL_ESHAPE, "score: Hq/Hkv = %d exceeds %d", d.Hq / d.Hkv, kMaxGroup);
+    if (d.k_strides[2] * (d.dtype == ZIPVL_BF16 ? 2 : 4) > (1 << 22))       // 256 staged rows must span less than 2 GiB
+        return set_error(ZIPVL_ESHAPE, "score: K token stride of %lld elements is too large", (long long)d.k_strides[2]);
     ProbeList pl;
     for (int t = 0; t < ZIPVL_MAX_PROBES; ++t) pl.pos[t] = t < m ? probe_pos[t] : -1;
     const int n_eff = probe_pos[m - 1] + 1;
     if (d.dtype == ZIPVL_BF16) {
-        if (d.d == 128) return launch_score_nb<__bf16, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-        return launch_score_nb<__bf16, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+        if (d.d == 128) return launch_score_t<__bf16, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+        return launch_score_t<__bf16, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
     }
-    if (d.d == 128) return launch_score_nb<float, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-    return launch_score_nb<float, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    if (d.d == 128) return launch_score_t<float, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    return launch_score_t<float, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
 }
 
 }  // namespace zipvl
