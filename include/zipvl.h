@@ -128,7 +128,11 @@ int zipvl_score_all_rows(const void* Q, const void* K, const zipvl_dims* dims, f
  *
  * mass [device] [units,n] fp32; rank [device] same shape or NULL (use mass for both steps)
  * tau in (0,1];  idx [device] [units,n] int32;  k [device] [units] int32
- * ws may be NULL (no workspace is needed; the arguments exist for symmetry).
+ * ws [device] may be NULL: one kernel, one workgroup per unit.  With a workspace of
+ * zipvl_workspace_bytes(ZIPVL_OP_SELECT, dims with B * Hkv = units, 0) bytes (16-byte aligned) the first,
+ * widest digit of the search is histogrammed by the whole chip and one workgroup per unit finishes (two
+ * kernels; faster for long vectors on few units).  That workspace must be ZERO before the first call that uses
+ * it; every call leaves it zero; two calls that overlap on one workspace race.  Same results either way.
  */
 int zipvl_select(const float* mass, const float* rank, int units, int n, double tau,
                  int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, void* stream);

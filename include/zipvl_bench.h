@@ -40,7 +40,8 @@ extern "C" {
 #define ZIPVL_K_PROBE_MFMA     17
 #define ZIPVL_K_PROBE_READ     18
 #define ZIPVL_K_DECODE_STEP    19
-#define ZIPVL_K_COUNT          20
+#define ZIPVL_K_SELECT_HIST    20
+#define ZIPVL_K_COUNT          21
 int zipvl_timing_enable(int on);
 int zipvl_timing_read(int kernel_id, double* total_ms, int* launches);
 

@@ -143,6 +143,13 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
+def _dense(*tensors):
+    """The library addresses these arrays as contiguous rows: refuse views with other strides."""
+    for t in tensors:
+        if t is not None and not t.is_contiguous():
+            raise ZipvlError(-1, f"expected a contiguous tensor, got strides {tuple(t.stride())} for shape {tuple(t.shape)}")
+
+
 def _stream() -> C.c_void_p:
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -175,16 +182,24 @@ def zipvl_score(Q: torch.Tensor, K: torch.Tensor, probe_pos: Sequence[int], soft
     return mass, rank
 
 
+def select_workspace(units: int, device) -> torch.Tensor:
+    """A zero-filled workspace for the two-kernel form of zipvl_select (kept between calls: every call leaves it zero)."""
+    dm = dims_of(None, None, None, B=units, Hq=1, Hkv=1, n=64, d=64, dtype=0)
+    return torch.zeros(max(256, workspace_bytes(OP_SELECT, dm)), dtype=torch.uint8, device=device)
+
+
 def zipvl_select(mass: torch.Tensor, rank: Optional[torch.Tensor], tau: float, *,
-                 idx: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None):
-    """(idx [units,n] int32 with the first k entries valid and ascending, k [units] int32)."""
+                 idx: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+    """(idx [units,n] int32 with the first k entries valid and ascending, k [units] int32).  ws: select_workspace(units)
+    for the two-kernel form, None for the one-kernel form."""
     lib = load_library()
+    _dense(mass, rank, idx, k)
     units, n = mass.shape
     if idx is None:
         idx = torch.empty((units, n), dtype=torch.int32, device=mass.device)
     if k is None:
         k = torch.empty((units,), dtype=torch.int32, device=mass.device)
-    _check(lib.zipvl_select(_ptr(mass), _ptr(rank), units, n, float(tau), _ptr(idx), _ptr(k), None, 0, _stream()))
+    _check(lib.zipvl_select(_ptr(mass), _ptr(rank), units, n, float(tau), _ptr(idx), _ptr(k), _ptr(ws), 0 if ws is None else ws.numel(), _stream()))
     return idx, k
 
 
@@ -210,6 +225,7 @@ def zipvl_share_scores(mass: torch.Tensor, rank: Optional[torch.Tensor], B: int,
                        mass_b: Optional[torch.Tensor] = None, rank_b: Optional[torch.Tensor] = None):
     """(mass_b, rank_b [B, n]): the per-unit scores [B*Hkv, n] averaged over the units of each batch element."""
     lib = load_library()
+    _dense(mass, rank, mass_b, rank_b)
     units, n = mass.shape
     Hkv = units // B
     if mass_b is None:
@@ -377,7 +393,7 @@ def zipvl_decode_attn_q(q: torch.Tensor, cache: QCache, softmax_scale: float, *,
 KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "kv_append", "zero_fill",
            "pack_kv", "flash_kept", "decode_partial", "decode_combine", "score_rowfinal", "share_scores",
            "token_slots", "quantize_rows", "decode_q_partial", "allrows_lse", "allrows_colsum", "probe_mfma", "probe_read",
-           "decode_step")
+           "decode_step", "select_hist")
 
 
 def zipvl_probe_peaks(device="cuda:0", iters: int = 4096, read_mib: int = 4096):

@@ -18,9 +18,11 @@
 // One 1024-thread workgroup per selection unit.  Up to n = 27648 the order-preserving keys of
 // the vector in use are held in LDS (read from memory once, coalesced); longer vectors are
 // re-read per digit and pass through LDS block by block for the emission.
+#include <algorithm>
 #include <atomic>
 
 #include "launch.h"
+#include "select_dev.h"
 
 namespace zipvl {
 
@@ -43,24 +45,6 @@ struct SelShared {
     uint32_t sole_key;     // the key of a bin's only element
     int k;
 };
-
-// Order-preserving 31-bit key of a non-negative fp32 score: its bit pattern.  Scores are >= 0 by
-// contract; anything with the sign bit set (-0 included) is ordered and summed as zero.
-__device__ __forceinline__ uint32_t orderable(float x) {
-    const uint32_t b = __float_as_uint(x);
-    return (b & 0x80000000u) ? 0u : b;
-}
-
-// floor(x * 2^40) for finite x in [0, 2^24), exact, integer-only.
-__device__ __forceinline__ unsigned long long fixed40(float x) {
-    const uint32_t b = __float_as_uint(x);
-    const int e = (b >> 23) & 255;
-    if ((b & 0x80000000u) || e == 0 || e == 255) return 0ull;
-    const unsigned long long M = (b & 0x7FFFFFu) | 0x800000u;     // x = M * 2^(e-150)
-    const int sh = e - 110;
-    if (sh >= 0) return M << (sh > 40 ? 40 : sh);
-    return (-sh >= 24) ? 0ull : (M >> (-sh));
-}
 
 // Where the keys of a unit live while the kernel runs: in LDS (filled once per vector with
 // coalesced reads, then read conflict-free by every pass) when they fit, otherwise every pass
@@ -86,10 +70,6 @@ __device__ __forceinline__ void fill_keys(uint32_t* dst, const float* __restrict
     for (int j = threadIdx.x; j < n; j += kSelThreads) dst[j] = orderable(x[j]);
 }
 
-__device__ __forceinline__ unsigned long long fixed40_of_key(uint32_t key) {
-    return fixed40(__uint_as_float(key));
-}
-
 // One descent over the 31 key bits in four digits, exponent byte first (8 + 8 + 8 + 7 bits).  The
 // first two digits see many elements and spread them over kRep histogram replicas chosen by the
 // lane (replica r of digit v sits at slot r * 257 + v: the lanes of a wave that share a digit hit
@@ -98,7 +78,6 @@ __device__ __forceinline__ unsigned long long fixed40_of_key(uint32_t key) {
 // element count (bits 41..63) over the integer score sum (bits 0..40, sum of a unit < 2^41), one LDS
 // atomic per element, and the descent crosses on the sum (target fixed after the first digit from
 // the grand total); otherwise slots are plain counts and the descent crosses on cnt_target.
-constexpr int kSumBits = 41;
 constexpr int kRep = kSelRep, kRepStride = kSelRepStride;
 
 template <bool WITH_SUM>
@@ -358,20 +337,87 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
 }
 
-int launch_select(const float* mass, const float* rank, int units, int n, double tau,
-                  int32_t* idx, int32_t* k, hipStream_t st)
+// ---------------------------------------------------------------- two kernels: parallel first digit, then one workgroup per unit
+// First-digit histograms of a slice of positions, built in LDS and added to the unit's tables.
+__global__ __launch_bounds__(256) void select_hist_kernel(
+    const float* __restrict__ mass_all, const float* __restrict__ rank_all, int n, int slice,
+    unsigned long long* __restrict__ hm_all, uint32_t* __restrict__ hr_all)
 {
-    const int in_lds = n <= kSelMaxLdsKeys ? 1 : 0;
-    // the key area also stages the blocks of a longer vector for the emission
-    const size_t dyn = (size_t)(in_lds ? n : kSelMaxLdsKeys) * sizeof(uint32_t);
+    __shared__ unsigned long long lm[kSelBins];
+    __shared__ uint32_t lr[kSelBins];
+    const int u = blockIdx.y, tid = threadIdx.x;
+    const int j0 = blockIdx.x * slice, j1 = min(n, j0 + slice);
+    if (j0 >= j1) return;
+    for (int b = tid; b < kSelBins; b += 256) { lm[b] = 0ull; lr[b] = 0u; }
+    __syncthreads();
+    const float* mass = mass_all + (int64_t)u * n;
+    const float* rank = rank_all ? rank_all + (int64_t)u * n : nullptr;
+    for (int j = j0 + tid; j < j1; j += 256) {
+        const uint32_t key = orderable(mass[j]);
+        atomicAdd(&lm[key >> kSelBinShift], (1ull << kSumBits) + fixed40_of_key(key));
+        if (rank) atomicAdd(&lr[orderable(rank[j]) >> kSelBinShift], 1u);
+    }
+    __syncthreads();
+    flush_tables<256>(lm, lr, hm_all + (int64_t)u * kSelBins, rank ? hr_all + (int64_t)u * kSelBins : nullptr);
+}
+
+// The rest of the selection of one unit; leaves the unit's tables zero for the next call.
+__global__ __launch_bounds__(kSelThreads) void select_tail_kernel(
+    const float* __restrict__ mass_all, const float* __restrict__ rank_all, int n, double tau,
+    unsigned long long* __restrict__ hm_all, uint32_t* __restrict__ hr_all,
+    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out, int key_cap)
+{
+    __shared__ TailShared sh;
+    extern __shared__ uint32_t lds_keys[];
+    const int u = blockIdx.x;
+    const float* mass = mass_all + (int64_t)u * n;
+    unsigned long long* hm = hm_all + (int64_t)u * kSelBins;
+    uint32_t* hr = hr_all + (int64_t)u * kSelBins;
+    select_tail<kSelThreads, false>(mass, rank_all ? rank_all + (int64_t)u * n : mass, n, tau, hm, rank_all ? hr : nullptr,
+                                    idx_all + (int64_t)u * n, k_out + u, lds_keys, key_cap, sh);
+    __syncthreads();
+    for (int b = threadIdx.x; b < kSelBins; b += kSelThreads) { hm[b] = 0ull; hr[b] = 0u; }
+}
+
+size_t select_workspace_bytes(int units) {
+    return (size_t)units * kSelBins * (sizeof(unsigned long long) + sizeof(uint32_t));
+}
+
+int launch_select(const float* mass, const float* rank, int units, int n, double tau,
+                  int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, hipStream_t st)
+{
     static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kSelMaxLdsKeys * (int)sizeof(uint32_t)) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(&select_tail_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kSelMaxLdsKeys * (int)sizeof(uint32_t)) != hipSuccess)
             return set_error(ZIPVL_EHIP, "select: cannot reserve LDS for the keys");
         attr_done = true;
     }
+    const int in_lds = n <= kSelMaxLdsKeys ? 1 : 0;
+    if (ws && ws_bytes >= select_workspace_bytes(units) && tau < 1.0) {
+        // two kernels: the first digit of both descents from every CU, then one workgroup per unit
+        unsigned long long* hm = (unsigned long long*)ws;
+        uint32_t* hr = (uint32_t*)(hm + (size_t)units * kSelBins);
+        const int slices = std::max(1, std::min((n + 255) / 256, (512 + units - 1) / units));
+        const int slice = ((n + slices - 1) / slices + 63) / 64 * 64;
+        {
+            KernelTimer tm(ZIPVL_K_SELECT_HIST, st);
+            hipLaunchKernelGGL(select_hist_kernel, dim3((n + slice - 1) / slice, units), dim3(256), 0, st, mass, rank, n, slice, hm, hr);
+        }
+        int rc = check_launch("select_hist");
+        if (rc) return rc;
+        const int key_cap = in_lds ? (n + 31) / 32 * 32 : kSelMaxLdsKeys;
+        KernelTimer tm(ZIPVL_K_SELECT, st);
+        hipLaunchKernelGGL(select_tail_kernel, dim3(units), dim3(kSelThreads), (size_t)key_cap * sizeof(uint32_t), st,
+                           mass, rank, n, tau, hm, hr, idx, k, key_cap);
+        return check_launch("select_tail");
+    }
+    // the key area also stages the blocks of a longer vector for the emission
+    const size_t dyn = (size_t)(in_lds ? n : kSelMaxLdsKeys) * sizeof(uint32_t);
     KernelTimer tm(ZIPVL_K_SELECT, st);
     hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), dyn, st, mass, rank, n, tau, idx, k, in_lds);
     return check_launch("select");

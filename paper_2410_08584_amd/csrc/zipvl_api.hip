@@ -105,7 +105,7 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m) {
     if (check_dims("zipvl_workspace_bytes", dims, false, false, false)) return 0;
     switch (op) {
         case ZIPVL_OP_SCORE: return score_workspace_bytes(*dims, m);
-        case ZIPVL_OP_SELECT: return 0;
+        case ZIPVL_OP_SELECT: return select_workspace_bytes(dims->B * dims->Hkv);
         case ZIPVL_OP_SPARSE_PREFILL: return prefill_workspace_bytes(*dims);
         case ZIPVL_OP_DECODE: return decode_workspace_bytes(*dims, dims->n);
         case ZIPVL_OP_QUANTIZE_KV: return quantize_workspace_bytes(*dims);
@@ -163,7 +163,6 @@ int zipvl_select(const float* mass, const float* rank, int units, int n, double 
                  int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, void* stream)
 {
     const char* fn = "zipvl_select";
-    (void)ws; (void)ws_bytes;
     if (!mass || !idx || !k) return set_error(ZIPVL_EINVAL, "%s: mass, idx and k must not be NULL", fn);
     if (units < 1 || n < 1) return set_error(ZIPVL_EINVAL, "%s: units and n must be positive (got %d, %d)", fn, units, n);
     if (n >= (1 << 23)) return set_error(ZIPVL_ESHAPE, "%s: n = %d must be below 2^23", fn, n);
@@ -171,7 +170,10 @@ int zipvl_select(const float* mass, const float* rank, int units, int n, double 
     if ((reinterpret_cast<uintptr_t>(mass) | reinterpret_cast<uintptr_t>(rank) |
          reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(k)) & 3u)
         return set_error(ZIPVL_EALIGN, "%s: pointers must be 4-byte aligned", fn);
-    return launch_select(mass, rank, units, n, tau, idx, k, (hipStream_t)stream);
+    if (ws && (reinterpret_cast<uintptr_t>(ws) & 15u)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
+    if (ws && ws_bytes < select_workspace_bytes(units))
+        return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given (or pass NULL)", fn, select_workspace_bytes(units), ws_bytes);
+    return launch_select(mass, rank, units, n, tau, idx, k, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int zipvl_share_scores(const float* mass, const float* rank, int B, int Hkv, int n,

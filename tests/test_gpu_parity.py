@@ -85,17 +85,27 @@ def test_compact_kv_bit_exact(dtype, d):
 
 
 # ------------------------------------------------------------------ selection
+SELECT_WS = {}
+
+
 def _select_case(name, mass, rank, tau):
     say(f"select case={name} units={mass.shape[0]} n={mass.shape[1]} tau={tau}")
+    mass = np.ascontiguousarray(mass)
+    rank = None if rank is None else np.ascontiguousarray(rank)
     m_d = torch.from_numpy(mass).to(DEV)
     r_d = None if rank is None else torch.from_numpy(rank).to(DEV)
-    idx, k = z.zipvl_select(m_d, r_d, tau)
-    torch.cuda.synchronize()
-    idx, k = idx.cpu().numpy(), k.cpu().numpy()
-    for u in range(mass.shape[0]):
-        p, T = oz.select(mass[u], None if rank is None else rank[u], tau)
-        assert k[u] == p, f"{name} unit {u}: k {k[u]} != {p}"
-        assert np.array_equal(idx[u, :p], T), f"{name} unit {u}: index set differs"
+    units = mass.shape[0]
+    ws = SELECT_WS.setdefault(units, z.select_workspace(units, DEV))      # reused across cases: every call must leave it zero
+    ref = [oz.select(mass[u], None if rank is None else rank[u], tau) for u in range(units)]
+    for form, w_ in (("one kernel", None), ("two kernels", ws)):
+        idx, k = z.zipvl_select(m_d, r_d, tau, ws=w_)
+        torch.cuda.synchronize()
+        idx, k = idx.cpu().numpy(), k.cpu().numpy()
+        for u in range(units):
+            p, T = ref[u]
+            assert k[u] == p, f"{name} ({form}) unit {u}: k {k[u]} != {p}"
+            assert np.array_equal(idx[u, :p], T), f"{name} ({form}) unit {u}: index set differs"
+    assert int(ws.view(torch.int32).abs().sum().item()) == 0, f"{name}: the workspace was not left zero"
 
 
 def test_select_exact_on_synthetic_distributions():
@@ -133,6 +143,15 @@ def test_select_exact_on_synthetic_distributions():
     tail = norm(np.concatenate([r.random((2, 40)) * 50, r.random((2, 18392)) * 0.01], axis=1))
     rk = tail.copy(); rk[:, -64:] *= np.linspace(1, 64, 64, dtype=np.float32)
     _select_case("heavy+tail", tail, rk, 0.975)
+    # one first-digit bin (a sixteenth of a binade) holding more elements than the gathered list takes, and exactly as many
+    for cnt in (2048, 2049, 5000):
+        band = (1.0 + r.random((2, cnt)) / 17.0).astype(np.float32)        # all in [1, 1 + 1/16): one bin
+        rest = (r.random((2, 3000)) * 0.9).astype(np.float32)
+        x = norm(np.concatenate([rest, band], axis=1)[:, r.permutation(3000 + cnt)])
+        _select_case(f"crowded-bin-{cnt}", x, (x * (1 + 0.01 * r.random(x.shape))).astype(np.float32), 0.6)
+        _select_case(f"crowded-bin-single-{cnt}", x, None, 0.5)
+    dup = norm(np.repeat(r.random((2, 40)) ** 3, 100, axis=1)[:, r.permutation(4000)])      # 40 distinct values, 100 copies each
+    _select_case("blocks-of-equal-values", dup, dup[:, ::-1].copy(), 0.8)
 
 
 # ------------------------------------------------------------------ scores

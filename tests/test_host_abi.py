@@ -43,7 +43,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_workspace_sizes(lib):
     dm = _dims(B=1, Hq=28, Hkv=4, n=18432, d=128, dtype=1)
     assert z.workspace_bytes(z.OP_SPARSE_PREFILL, dm) == 2 * 4 * 18432 * 128 * 2
-    assert z.workspace_bytes(z.OP_SELECT, dm) == 0
+    assert z.workspace_bytes(z.OP_SELECT, dm) == 4 * 4096 * 12      # per unit: 4096 packed 64-bit slots and 4096 counts
     assert z.workspace_bytes(z.OP_SCORE, dm, 64) > 0
     assert z.workspace_bytes(z.OP_DECODE, dm) > 0
     # the fused decode step adds one 256-byte-rounded block of per-unit arrival counters in front of the partial states
