@@ -64,6 +64,15 @@ extern "C" {
 /* flag of zipvl_sparse_prefill and zipvl_compact_kv */
 #define ZIPVL_T_PER_BATCH         4  /* idx is [B,n], k is [B]: one important set serves every head of a batch element */
 
+/* flags of zipvl_score */
+#define ZIPVL_SCORE_GROUP_MEAN    0  /* one row of scores per (batch, KV head): the mean over the query heads of the group */
+#define ZIPVL_SCORE_PER_QHEAD     1  /* one row per (batch, query head): mass, rank are [B*Hq, n], nothing is averaged */
+
+/* bits of the status word of zipvl_select (what its contract excludes, seen in a unit's input) */
+#define ZIPVL_SELECT_NEGATIVE     1  /* an entry with the sign bit set: ordered and summed as zero */
+#define ZIPVL_SELECT_NONFINITE    2  /* an infinity or NaN: ordered by its bit pattern, summed as zero */
+#define ZIPVL_SELECT_OVERFLOW     4  /* mass sums to 2 or more: the integer sum does not fit, k is unreliable */
+
 typedef struct zipvl_dims {
     int32_t B, Hq, Hkv, n, d;
     int32_t dtype;            /* ZIPVL_F32 | ZIPVL_BF16 */
@@ -88,6 +97,8 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m);
  *   a_j     = sum_c A'[c,j]
  *   mass[u,j] = mean over the G heads of the group of  a_j / m
  *   rank[u,j] = mean over the G heads of the group of  a_j / #{c : P_c >= j}   (0 if none)
+ * flags: ZIPVL_SCORE_GROUP_MEAN (default, rows u = b*Hkv + g) or ZIPVL_SCORE_PER_QHEAD (no mean: one row per query
+ * head, u = b*Hq + h, mass and rank [B*Hq, n]; the paper writes its equations for a single head).
  *
  * Q [device]          [B,Hq,n,d] by q_strides (only the probe rows are read)
  * K [device]          [B,Hkv,n,d] by k_strides
@@ -97,7 +108,7 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m);
  * A' is never written to memory.  mass of a unit sums to 1 (up to fp32 rounding).
  */
 int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims,
-                const int32_t* probe_pos, int m, float softmax_scale,
+                const int32_t* probe_pos, int m, float softmax_scale, int flags,
                 float* mass, float* rank, void* ws, size_t ws_bytes, void* stream);
 
 /*
@@ -128,6 +139,10 @@ int zipvl_score_all_rows(const void* Q, const void* K, const zipvl_dims* dims, f
  *
  * mass [device] [units,n] fp32; rank [device] same shape or NULL (use mass for both steps)
  * tau in (0,1];  idx [device] [units,n] int32;  k [device] [units] int32
+ * status [device] [units] int32 or NULL: when given, every unit's inputs are checked on the device against the
+ * contract above (one more pass over them) and status[u] receives ZIPVL_SELECT_* bits, 0 if all is well; nothing
+ * is read back and the selection runs either way (validation that needs device data cannot be an error code of a
+ * call that does not synchronise).
  * ws [device] may be NULL: one kernel, one workgroup per unit.  With a workspace of
  * zipvl_workspace_bytes(ZIPVL_OP_SELECT, dims with B * Hkv = units, 0) bytes (16-byte aligned) the first,
  * widest digit of the search is histogrammed by the whole chip and one workgroup per unit finishes (two
@@ -135,7 +150,7 @@ int zipvl_score_all_rows(const void* Q, const void* K, const zipvl_dims* dims, f
  * it; every call leaves it zero; two calls that overlap on one workspace race.  Same results either way.
  */
 int zipvl_select(const float* mass, const float* rank, int units, int n, double tau,
-                 int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, void* stream);
+                 int32_t* idx, int32_t* k, int32_t* status, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * One important set per layer instead of one per KV head.  Paper: Algorithm 1 as written selects a

@@ -12,6 +12,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libzipvl.so"
 
 OUT_FULL, OUT_COMPACT, KV_ALREADY_COMPACT, T_PER_BATCH = 0, 1, 2, 4
+SCORE_PER_QHEAD = 1
+SELECT_NEGATIVE, SELECT_NONFINITE, SELECT_OVERFLOW = 1, 2, 4
 OP_SCORE, OP_SELECT, OP_SPARSE_PREFILL, OP_DECODE, OP_QUANTIZE_KV, OP_DECODE_Q, OP_SCORE_ALL_ROWS, OP_DECODE_STEP = 1, 2, 3, 4, 5, 6, 7, 8
 
 EXPORTS = ("zipvl_version", "zipvl_last_error", "zipvl_workspace_bytes", "zipvl_score", "zipvl_select",
@@ -58,9 +60,9 @@ def load_library():
     lib.zipvl_last_error.restype = C.c_char_p
     lib.zipvl_workspace_bytes.restype = C.c_size_t
     lib.zipvl_workspace_bytes.argtypes = [C.c_int, C.POINTER(Dims), C.c_int]
-    lib.zipvl_score.argtypes = [vp, vp, C.POINTER(Dims), C.POINTER(C.c_int32), C.c_int, C.c_float,
+    lib.zipvl_score.argtypes = [vp, vp, C.POINTER(Dims), C.POINTER(C.c_int32), C.c_int, C.c_float, C.c_int,
                                 f32p, f32p, vp, C.c_size_t, vp]
-    lib.zipvl_select.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_double, i32p, i32p, vp, C.c_size_t, vp]
+    lib.zipvl_select.argtypes = [f32p, f32p, C.c_int, C.c_int, C.c_double, i32p, i32p, i32p, vp, C.c_size_t, vp]
     lib.zipvl_sparse_prefill.argtypes = [vp, vp, vp, C.POINTER(Dims), i32p, i32p, C.c_float, C.c_int,
                                          vp, vp, C.c_size_t, vp]
     lib.zipvl_compact_kv.argtypes = [vp, vp, C.POINTER(Dims), i32p, i32p, vp, vp, C.c_int32, i32p, C.c_int, vp]
@@ -164,11 +166,11 @@ def _workspace(nbytes: int, device) -> torch.Tensor:
 
 def zipvl_score(Q: torch.Tensor, K: torch.Tensor, probe_pos: Sequence[int], softmax_scale: float, *,
                 mass: Optional[torch.Tensor] = None, rank: Optional[torch.Tensor] = None,
-                want_rank: bool = True, ws: Optional[torch.Tensor] = None):
-    """(mass, rank) fp32 [B*Hkv, n] from the probe rows of Q against K."""
+                want_rank: bool = True, ws: Optional[torch.Tensor] = None, flags: int = 0):
+    """(mass, rank) fp32 [B*Hkv, n] from the probe rows of Q against K ([B*Hq, n] with flags=SCORE_PER_QHEAD)."""
     lib = load_library()
     dm = dims_of(Q, K)
-    units = dm.B * dm.Hkv
+    units = dm.B * (dm.Hq if flags & SCORE_PER_QHEAD else dm.Hkv)
     pp = [int(p) for p in probe_pos]
     arr = (C.c_int32 * max(len(pp), 1))(*pp)
     if mass is None:
@@ -177,7 +179,8 @@ def zipvl_score(Q: torch.Tensor, K: torch.Tensor, probe_pos: Sequence[int], soft
         rank = torch.empty((units, dm.n), dtype=torch.float32, device=Q.device)
     if ws is None:
         ws = _workspace(workspace_bytes(OP_SCORE, dm, len(pp)), Q.device)
-    _check(lib.zipvl_score(_ptr(Q), _ptr(K), C.byref(dm), arr, len(pp), float(softmax_scale),
+    _dense(mass, rank)
+    _check(lib.zipvl_score(_ptr(Q), _ptr(K), C.byref(dm), arr, len(pp), float(softmax_scale), int(flags),
                            _ptr(mass), _ptr(rank), _ptr(ws), ws.numel(), _stream()))
     return mass, rank
 
@@ -189,9 +192,10 @@ def select_workspace(units: int, device) -> torch.Tensor:
 
 
 def zipvl_select(mass: torch.Tensor, rank: Optional[torch.Tensor], tau: float, *,
-                 idx: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None):
+                 idx: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                 status: Optional[torch.Tensor] = None):
     """(idx [units,n] int32 with the first k entries valid and ascending, k [units] int32).  ws: select_workspace(units)
-    for the two-kernel form, None for the one-kernel form."""
+    for the two-kernel form, None for the one-kernel form.  status: int32 [units] tensor that receives the SELECT_* bits."""
     lib = load_library()
     _dense(mass, rank, idx, k)
     units, n = mass.shape
@@ -199,7 +203,8 @@ def zipvl_select(mass: torch.Tensor, rank: Optional[torch.Tensor], tau: float, *
         idx = torch.empty((units, n), dtype=torch.int32, device=mass.device)
     if k is None:
         k = torch.empty((units,), dtype=torch.int32, device=mass.device)
-    _check(lib.zipvl_select(_ptr(mass), _ptr(rank), units, n, float(tau), _ptr(idx), _ptr(k), _ptr(ws), 0 if ws is None else ws.numel(), _stream()))
+    _check(lib.zipvl_select(_ptr(mass), _ptr(rank), units, n, float(tau), _ptr(idx), _ptr(k), _ptr(status), _ptr(ws),
+                            0 if ws is None else ws.numel(), _stream()))
     return idx, k
 
 

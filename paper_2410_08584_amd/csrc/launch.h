@@ -18,11 +18,11 @@ struct ProbeList {            // passed by value in the kernel arguments
 
 size_t score_workspace_bytes(const zipvl_dims& d, int m);
 int launch_score(const void* Q, const void* K, const zipvl_dims& d, const int32_t* probe_pos, int m,
-                 float scale, float* mass, float* rank, void* ws, hipStream_t st);
+                 float scale, int flags, float* mass, float* rank, void* ws, hipStream_t st);
 
 size_t select_workspace_bytes(int units);
 int launch_select(const float* mass, const float* rank, int units, int n, double tau,
-                  int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, hipStream_t st);
+                  int32_t* idx, int32_t* k, int32_t* status, void* ws, size_t ws_bytes, hipStream_t st);
 
 size_t prefill_workspace_bytes(const zipvl_dims& d);
 int launch_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims& d,

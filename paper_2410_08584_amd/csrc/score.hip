@@ -56,7 +56,7 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
     const T* __restrict__ Q, const T* __restrict__ K,
     int64_t qs0, int64_t qs1, int64_t qs2, int64_t ks0, int64_t ks1, int64_t ks2,
     ProbeList probes, int m, int NB, int n, int n_eff, float c, float2* __restrict__ partial, int nsplit, int bpc,
-    float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv)
+    float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv, int kv_div)
 {
     using C = ScoreCfg<T, D>;
     constexpr int CH = C::CH, RB = C::RB, SK = C::SK, KBS = C::KBS;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
     const int slot = few ? w / NT : 0;
 
     // where this lane's NLD 16-byte pieces of a stage come from: row inside the stage and chunk under the row swizzle
-    const char* Ku = reinterpret_cast<const char*>(K + b * ks0 + g * ks1);
+    const char* Ku = reinterpret_cast<const char*>(K + b * ks0 + (g / kv_div) * ks1);   // kv_div > 1: every query head is its own unit
     const int row_stride = (int)ks2 * C::E;                          // bytes; a stage spans less than 2 GiB (checked on the host)
     const unsigned lds0 = lds_address(kstage);
     // where this lane's NLD 16-byte pieces of a stage come from: byte offset of (row inside the stage, chunk under the row swizzle)
@@ -299,7 +299,7 @@ size_t score_workspace_bytes(const zipvl_dims& d, int m) {
 
 template <typename T, int D, int NWV>
 static int launch_score_w(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
-                          int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
+                          int n_eff, float scale, float* mass, float* rank, void* ws, int kv_div, hipStream_t st)
 {
     using C = ScoreCfg<T, D>;
     const float c = scale * kLog2e;
@@ -324,7 +324,7 @@ static int launch_score_w(const void* Q, const void* K, const zipvl_dims& d, con
         hipLaunchKernelGGL((score_kernel<T, D, 1, NWV>), dim3(nsplit, units), dim3(64 * NWV), lds, st,
             (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
             d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, NB, d.n, n_eff, c, partial, nsplit, bpc1,
-            (float*)nullptr, (float*)nullptr, d.Hq, d.Hkv);
+            (float*)nullptr, (float*)nullptr, d.Hq, d.Hkv, kv_div);
     }
     int rc = check_launch("score_rowstats");
     if (rc) return rc;
@@ -332,34 +332,42 @@ static int launch_score_w(const void* Q, const void* K, const zipvl_dims& d, con
     hipLaunchKernelGGL((score_kernel<T, D, 2, NWV>), dim3(chunks2, units), dim3(64 * NWV), lds, st,
         (const T*)Q, (const T*)K, d.q_strides[0], d.q_strides[1], d.q_strides[2],
         d.k_strides[0], d.k_strides[1], d.k_strides[2], pl, m, NB, d.n, n_eff, c, partial, nsplit, bpc2,
-        mass, rank, d.Hq, d.Hkv);
+        mass, rank, d.Hq, d.Hkv, kv_div);
     return check_launch("score_colsum");
 }
 
 template <typename T, int D>
 static int launch_score_t(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
-                          int n_eff, float scale, float* mass, float* rank, void* ws, hipStream_t st)
+                          int n_eff, float scale, float* mass, float* rank, void* ws, int kv_div, hipStream_t st)
 {
-    const int NT = (d.Hq / d.Hkv) * (probe_rows(m) / 32);            // (head, probe block) tasks per KV head
-    if (NT > 8) return launch_score_w<T, D, 16>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-    return launch_score_w<T, D, 8>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    const int NT = (d.Hq / d.Hkv) * (probe_rows(m) / 32);            // (head, probe block) tasks per unit
+    if (NT > 8) return launch_score_w<T, D, 16>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, kv_div, st);
+    return launch_score_w<T, D, 8>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, kv_div, st);
 }
 
-int launch_score(const void* Q, const void* K, const zipvl_dims& d, const int32_t* probe_pos, int m,
-                 float scale, float* mass, float* rank, void* ws, hipStream_t st)
+int launch_score(const void* Q, const void* K, const zipvl_dims& d0, const int32_t* probe_pos, int m,
+                 float scale, int flags, float* mass, float* rank, void* ws, hipStream_t st)
 {
-    if (d.Hq / d.Hkv > kMaxGroup) return set_error(ZIPVL_ESHAPE, "score: Hq/Hkv = %d exceeds %d", d.Hq / d.Hkv, kMaxGroup);
+    // one row of scores per query head: the same kernels on dims in which every query head is a unit of its own
+    // that reads the K of the KV head it belongs to
+    zipvl_dims d = d0;
+    int kv_div = 1;
+    if ((flags & ZIPVL_SCORE_PER_QHEAD) && d0.Hq != d0.Hkv) {
+        kv_div = d0.Hq / d0.Hkv;
+        d.Hkv = d0.Hq;
+    }
+    if (d0.Hq / d0.Hkv > kMaxGroup) return set_error(ZIPVL_ESHAPE, "score: Hq/Hkv = %d exceeds %d", d0.Hq / d0.Hkv, kMaxGroup);
     if (d.k_strides[2] * (d.dtype == ZIPVL_BF16 ? 2 : 4) > (1 << 22))       // 256 staged rows must span less than 2 GiB
         return set_error(ZIPVL_ESHAPE, "score: K token stride of %lld elements is too large", (long long)d.k_strides[2]);
     ProbeList pl;
     for (int t = 0; t < ZIPVL_MAX_PROBES; ++t) pl.pos[t] = t < m ? probe_pos[t] : -1;
     const int n_eff = probe_pos[m - 1] + 1;
     if (d.dtype == ZIPVL_BF16) {
-        if (d.d == 128) return launch_score_t<__bf16, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-        return launch_score_t<__bf16, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+        if (d.d == 128) return launch_score_t<__bf16, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, kv_div, st);
+        return launch_score_t<__bf16, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, kv_div, st);
     }
-    if (d.d == 128) return launch_score_t<float, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
-    return launch_score_t<float, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, st);
+    if (d.d == 128) return launch_score_t<float, 128>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, kv_div, st);
+    return launch_score_t<float, 64>(Q, K, d, pl, m, n_eff, scale, mass, rank, ws, kv_div, st);
 }
 
 }  // namespace zipvl

@@ -202,7 +202,7 @@ __device__ void radix_descent(const Keys& keys, double tau, uint32_t cnt_target,
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ mass_all, const float* __restrict__ rank_all, int n, double tau,
-    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out, int keys_in_lds)
+    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out, int keys_in_lds, int32_t* __restrict__ status)
 {
     __shared__ SelShared sh;
     extern __shared__ uint32_t lds_keys[];             // kSelMaxLdsKeys entries
@@ -211,6 +211,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* mass = mass_all + (int64_t)u * n;
     const float* rank = rank_all ? rank_all + (int64_t)u * n : mass;
     int32_t* idx = idx_all + (int64_t)u * n;
+    if (status) {
+        const uint32_t f = input_flags<kSelThreads>(mass, rank, n, &sh.base_sum, &sh.sel_cnt);
+        if (tid == 0) status[u] = (int32_t)f;
+        __syncthreads();
+    }
 
     if (tau >= 1.0) {
         if (tid == 0) k_out[u] = n;
@@ -365,12 +370,17 @@ __global__ __launch_bounds__(256) void select_hist_kernel(
 __global__ __launch_bounds__(kSelThreads) void select_tail_kernel(
     const float* __restrict__ mass_all, const float* __restrict__ rank_all, int n, double tau,
     unsigned long long* __restrict__ hm_all, uint32_t* __restrict__ hr_all,
-    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out, int key_cap)
+    int32_t* __restrict__ idx_all, int32_t* __restrict__ k_out, int key_cap, int32_t* __restrict__ status)
 {
     __shared__ TailShared sh;
     extern __shared__ uint32_t lds_keys[];
     const int u = blockIdx.x;
     const float* mass = mass_all + (int64_t)u * n;
+    if (status) {
+        const uint32_t f = input_flags<kSelThreads>(mass, rank_all ? rank_all + (int64_t)u * n : mass, n, &sh.base_sum, &sh.sel_cnt);
+        if (threadIdx.x == 0) status[u] = (int32_t)f;
+        __syncthreads();
+    }
     unsigned long long* hm = hm_all + (int64_t)u * kSelBins;
     uint32_t* hr = hr_all + (int64_t)u * kSelBins;
     select_tail<kSelThreads, false>(mass, rank_all ? rank_all + (int64_t)u * n : mass, n, tau, hm, rank_all ? hr : nullptr,
@@ -384,7 +394,7 @@ size_t select_workspace_bytes(int units) {
 }
 
 int launch_select(const float* mass, const float* rank, int units, int n, double tau,
-                  int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, hipStream_t st)
+                  int32_t* idx, int32_t* k, int32_t* status, void* ws, size_t ws_bytes, hipStream_t st)
 {
     static std::atomic<bool> attr_done{false};
     if (!attr_done) {
@@ -413,13 +423,13 @@ int launch_select(const float* mass, const float* rank, int units, int n, double
         const int key_cap = in_lds ? (n + 31) / 32 * 32 : kSelMaxLdsKeys;
         KernelTimer tm(ZIPVL_K_SELECT, st);
         hipLaunchKernelGGL(select_tail_kernel, dim3(units), dim3(kSelThreads), (size_t)key_cap * sizeof(uint32_t), st,
-                           mass, rank, n, tau, hm, hr, idx, k, key_cap);
+                           mass, rank, n, tau, hm, hr, idx, k, key_cap, status);
         return check_launch("select_tail");
     }
     // the key area also stages the blocks of a longer vector for the emission
     const size_t dyn = (size_t)(in_lds ? n : kSelMaxLdsKeys) * sizeof(uint32_t);
     KernelTimer tm(ZIPVL_K_SELECT, st);
-    hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), dyn, st, mass, rank, n, tau, idx, k, in_lds);
+    hipLaunchKernelGGL(select_kernel, dim3(units), dim3(kSelThreads), dyn, st, mass, rank, n, tau, idx, k, in_lds, status);
     return check_launch("select");
 }
 

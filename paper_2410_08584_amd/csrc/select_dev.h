@@ -357,6 +357,33 @@ __device__ void emit_block(const uint32_t* lds_keys, int b0, int bn, uint32_t vs
     eq_run += tot_e;
 }
 
+// What the contract of the selection excludes, looked for in the inputs of one unit (one more pass over both
+// vectors, only when the caller asks for the status word): bit 0 an entry with the sign bit set (ordered and summed as
+// zero), bit 1 an infinity or NaN (ordered by its bits, summed as zero), bit 2 the integer sum of `mass` reaches
+// 2^41 (it no longer fits its field of a histogram slot: k is unreliable).  scratch: one 64-bit and one 32-bit
+// word of LDS.  Every thread returns the same flags.
+template <int NTH>
+__device__ uint32_t input_flags(const float* __restrict__ mass, const float* __restrict__ rank, int n,
+                                unsigned long long* sum_scratch, uint32_t* flag_scratch) {
+    if (threadIdx.x == 0) { *sum_scratch = 0ull; *flag_scratch = 0u; }
+    __syncthreads();
+    uint32_t f = 0;
+    unsigned long long s = 0;
+    for (int j = threadIdx.x; j < n; j += NTH) {
+        const uint32_t bm = __float_as_uint(mass[j]);
+        f |= (bm >> 31) | (((bm >> 23) & 255u) == 255u ? 2u : 0u);
+        s += fixed40(mass[j]);
+        if (rank != mass) {
+            const uint32_t br = __float_as_uint(rank[j]);
+            f |= (br >> 31) | (((br >> 23) & 255u) == 255u ? 2u : 0u);
+        }
+    }
+    if (f) atomicOr(flag_scratch, f);
+    if (s) atomicAdd(sum_scratch, s);
+    __syncthreads();
+    return *flag_scratch | (*sum_scratch >= (1ull << kSumBits) ? 4u : 0u);
+}
+
 // One unit, one workgroup of NTH threads: k from (mass, hm), T from (rank, hr) -> idx, k_out.
 // lds_keys: key_cap words of LDS (key_cap a multiple of 32).  rank == mass (and hr null): one vector for both steps.
 template <int NTH, bool COH>

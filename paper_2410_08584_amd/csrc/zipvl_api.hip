@@ -117,7 +117,7 @@ size_t zipvl_workspace_bytes(int op, const zipvl_dims* dims, int m) {
 }
 
 int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims, const int32_t* probe_pos, int m,
-                float softmax_scale, float* mass, float* rank, void* ws, size_t ws_bytes, void* stream)
+                float softmax_scale, int flags, float* mass, float* rank, void* ws, size_t ws_bytes, void* stream)
 {
     const char* fn = "zipvl_score";
     int rc = check_dims(fn, dims, true, true, false);
@@ -136,10 +136,11 @@ int zipvl_score(const void* Q, const void* K, const zipvl_dims* dims, const int3
             return set_error(ZIPVL_EINVAL, "%s: probe_pos must be strictly ascending (entry %d)", fn, t);
     }
     if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return set_error(ZIPVL_EINVAL, "%s: softmax_scale must be positive and finite", fn);
+    if (flags & ~ZIPVL_SCORE_PER_QHEAD) return set_error(ZIPVL_EUNSUPPORTED, "%s: unknown flags 0x%x", fn, flags);
     const size_t need = score_workspace_bytes(*dims, m);
     if (!ws || ws_bytes < need) return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given", fn, need, ws ? ws_bytes : (size_t)0);
     if (!aligned16(ws)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
-    return launch_score(Q, K, *dims, probe_pos, m, softmax_scale, mass, rank, ws, (hipStream_t)stream);
+    return launch_score(Q, K, *dims, probe_pos, m, softmax_scale, flags, mass, rank, ws, (hipStream_t)stream);
 }
 
 int zipvl_score_all_rows(const void* Q, const void* K, const zipvl_dims* dims, float softmax_scale,
@@ -160,7 +161,7 @@ int zipvl_score_all_rows(const void* Q, const void* K, const zipvl_dims* dims, f
 }
 
 int zipvl_select(const float* mass, const float* rank, int units, int n, double tau,
-                 int32_t* idx, int32_t* k, void* ws, size_t ws_bytes, void* stream)
+                 int32_t* idx, int32_t* k, int32_t* status, void* ws, size_t ws_bytes, void* stream)
 {
     const char* fn = "zipvl_select";
     if (!mass || !idx || !k) return set_error(ZIPVL_EINVAL, "%s: mass, idx and k must not be NULL", fn);
@@ -168,12 +169,12 @@ int zipvl_select(const float* mass, const float* rank, int units, int n, double 
     if (n >= (1 << 23)) return set_error(ZIPVL_ESHAPE, "%s: n = %d must be below 2^23", fn, n);
     if (!(tau > 0.0) || !(tau <= 1.0)) return set_error(ZIPVL_EINVAL, "%s: tau = %g is outside (0, 1]", fn, tau);
     if ((reinterpret_cast<uintptr_t>(mass) | reinterpret_cast<uintptr_t>(rank) |
-         reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(k)) & 3u)
+         reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(status)) & 3u)
         return set_error(ZIPVL_EALIGN, "%s: pointers must be 4-byte aligned", fn);
     if (ws && (reinterpret_cast<uintptr_t>(ws) & 15u)) return set_error(ZIPVL_EALIGN, "%s: ws is not 16-byte aligned", fn);
     if (ws && ws_bytes < select_workspace_bytes(units))
         return set_error(ZIPVL_EWORKSPACE, "%s: workspace of %zu bytes needed, %zu given (or pass NULL)", fn, select_workspace_bytes(units), ws_bytes);
-    return launch_select(mass, rank, units, n, tau, idx, k, ws, ws_bytes, (hipStream_t)stream);
+    return launch_select(mass, rank, units, n, tau, idx, k, status, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int zipvl_share_scores(const float* mass, const float* rank, int B, int Hkv, int n,

@@ -154,6 +154,59 @@ def test_select_exact_on_synthetic_distributions():
     _select_case("blocks-of-equal-values", dup, dup[:, ::-1].copy(), 0.8)
 
 
+def test_select_status_word_reports_inputs_outside_the_contract():
+    """The optional status word: 0 for valid input, and one bit each for a sign-bit entry, a non-finite entry and a
+    mass that sums to 2 or more; both forms of the call; the selection itself still runs (and, for the sign-bit
+    case, treats the entry as zero: the result equals the oracle's on the cleaned vector)."""
+    say("select status word")
+    r = np.random.Generator(np.random.PCG64(23))
+    n = 5000
+    good = r.random((5, n)).astype(np.float32) ** 4
+    good /= good.sum(axis=1, keepdims=True)
+    x = np.ascontiguousarray(good.astype(np.float32))
+    x[1, 17] = -x[1, 17]                         # negative entry
+    x[2, 4000] = np.float32("inf")               # infinity in mass
+    x[3] *= np.float32(2.5)                      # sums to 2.5: the integer sum no longer fits its field
+    rk = np.ascontiguousarray((good * (1 + r.random((5, n)))).astype(np.float32))
+    rk[4, 99] = np.float32("nan")                # NaN in rank only
+    ws = z.select_workspace(5, DEV)
+    expect = [0, z.SELECT_NEGATIVE, z.SELECT_NONFINITE, z.SELECT_OVERFLOW, z.SELECT_NONFINITE]
+    for w_ in (None, ws):
+        st = torch.full((5,), -1, dtype=torch.int32, device=DEV)
+        idx, k = z.zipvl_select(torch.from_numpy(x).to(DEV), torch.from_numpy(rk).to(DEV), 0.9, ws=w_, status=st)
+        torch.cuda.synchronize()
+        assert st.cpu().tolist() == expect, st.cpu().tolist()
+        for u in (0, 1):                         # valid unit, and the unit whose negative entry counts as zero
+            clean = np.where(np.signbit(x[u]), np.float32(0), x[u])
+            p, T = oz.select(clean, rk[u], 0.9)
+            assert int(k[u]) == p and np.array_equal(idx[u, :p].cpu().numpy(), T)
+    # without a status word nothing is written and valid input gives the same result
+    idx2, k2 = z.zipvl_select(torch.from_numpy(x[:1]).to(DEV), torch.from_numpy(rk[:1]).to(DEV), 0.9)
+    torch.cuda.synchronize()
+    assert int(k2[0]) == int(k[0]) and torch.equal(idx2[0, :int(k2[0])], idx[0, :int(k2[0])])
+
+
+def test_scores_per_query_head_are_the_single_head_scores():
+    """ZIPVL_SCORE_PER_QHEAD: one row per query head, nothing averaged (the paper's single-head equations); the group
+    mean of those rows is what the default mode returns."""
+    say("score per query head")
+    B, Hq, Hkv, n, d, dtype = 2, 6, 2, 777, 128, "bf16"
+    G = Hq // Hkv
+    w = make_custom(B, Hq, Hkv, n, d, dtype, seed=19)
+    Q, K = dev(w.Q, dtype), dev(w.K, dtype)
+    mass_h, rank_h = z.zipvl_score(Q, K, w.probe_pos, w.scale, flags=z.SCORE_PER_QHEAD)
+    mass_g, rank_g = z.zipvl_score(Q, K, w.probe_pos, w.scale)
+    torch.cuda.synchronize()
+    assert mass_h.shape == (B * Hq, n) and mass_g.shape == (B * Hkv, n)
+    mh, rh = host64(mass_h).reshape(B, Hq, n), host64(rank_h).reshape(B, Hq, n)
+    for b in range(B):
+        for h in range(Hq):
+            mo, ro = oz.token_scores(w.Q[b, h:h + 1], w.K[b, h // G:h // G + 1], w.probe_pos, w.scale)    # one head, its own KV head
+            assert_scores_close(mh[b, h][None], mo, dtype, "mass")
+            assert_scores_close(rh[b, h][None], ro, dtype, "rank")
+    np.testing.assert_allclose(mh.reshape(B, Hkv, G, n).mean(axis=2), host64(mass_g).reshape(B, Hkv, n), rtol=2e-6, atol=1e-12)
+
+
 # ------------------------------------------------------------------ scores
 SCORE_CASES = [
     # B, Hq, Hkv, n, d, dtype, m, probe

@@ -54,9 +54,9 @@ def test_workspace_sizes(lib):
 FAKE = C.c_void_p(0x1000)          # aligned, never dereferenced: every call below is rejected first
 
 
-def _score(lib, dm, probes, scale=0.125, Q=FAKE, K=FAKE, mass=FAKE, ws=FAKE, ws_bytes=1 << 30):
+def _score(lib, dm, probes, scale=0.125, Q=FAKE, K=FAKE, mass=FAKE, ws=FAKE, ws_bytes=1 << 30, flags=0):
     arr = (C.c_int32 * max(1, len(probes)))(*probes)
-    return lib.zipvl_score(Q, K, C.byref(dm), arr, len(probes), C.c_float(scale), mass, FAKE, ws, ws_bytes, None)
+    return lib.zipvl_score(Q, K, C.byref(dm), arr, len(probes), C.c_float(scale), flags, mass, FAKE, ws, ws_bytes, None)
 
 
 def test_score_rejects_bad_arguments(lib):
@@ -75,16 +75,19 @@ def test_score_rejects_bad_arguments(lib):
     assert _score(lib, _dims(), ok, scale=0.0) == -1
     assert _score(lib, _dims(), ok, ws=None) == -4
     assert _score(lib, _dims(), ok, ws_bytes=16) == -4 and "workspace" in z.zipvl_last_error()
+    assert _score(lib, _dims(), ok, flags=2) == -5 and "flags" in z.zipvl_last_error()
 
 
 def test_select_rejects_bad_arguments(lib):
     f = lib.zipvl_select
-    assert f(None, None, 1, 8, C.c_double(0.9), FAKE, FAKE, None, 0, None) == -1
-    assert f(FAKE, None, 0, 8, C.c_double(0.9), FAKE, FAKE, None, 0, None) == -1
-    assert f(FAKE, None, 1, 8, C.c_double(0.0), FAKE, FAKE, None, 0, None) == -1
-    assert f(FAKE, None, 1, 8, C.c_double(1.5), FAKE, FAKE, None, 0, None) == -1
-    assert f(FAKE, None, 1, 8, C.c_double(float("nan")), FAKE, FAKE, None, 0, None) == -1
-    assert f(C.c_void_p(0x1002), None, 1, 8, C.c_double(0.9), FAKE, FAKE, None, 0, None) == -3
+    assert f(None, None, 1, 8, C.c_double(0.9), FAKE, FAKE, None, None, 0, None) == -1
+    assert f(FAKE, None, 0, 8, C.c_double(0.9), FAKE, FAKE, None, None, 0, None) == -1
+    assert f(FAKE, None, 1, 8, C.c_double(0.0), FAKE, FAKE, None, None, 0, None) == -1
+    assert f(FAKE, None, 1, 8, C.c_double(1.5), FAKE, FAKE, None, None, 0, None) == -1
+    assert f(FAKE, None, 1, 8, C.c_double(float("nan")), FAKE, FAKE, None, None, 0, None) == -1
+    assert f(C.c_void_p(0x1002), None, 1, 8, C.c_double(0.9), FAKE, FAKE, None, None, 0, None) == -3
+    assert f(FAKE, None, 1, 8, C.c_double(0.9), FAKE, FAKE, C.c_void_p(0x1002), None, 0, None) == -3          # status word misaligned
+    assert f(FAKE, None, 1, 8, C.c_double(0.9), FAKE, FAKE, None, FAKE, 64, None) == -4 and "workspace" in z.zipvl_last_error()
 
 
 def test_prefill_compact_decode_reject_bad_arguments(lib):
