@@ -326,6 +326,12 @@ def run_stack(args):
         out["roofline"]["frac_of_measured_peak"] = res["evicted"]["GBps"] / gb
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_stack(samples, spec, tau, dense_flops, L)
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(out))
 
 

@@ -232,7 +232,8 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
                 // add the tasks' sums of stage s in task order and write the scores of its keys
                 const int row0 = sblk * 32;
                 const int keys = min(min(blk1 * 32, n) - row0, SK);
-                for (int t = tid; t < keys; t += kThreads) {
+                // (taken by the workgroup's last threads first: with more waves than tasks those waves are otherwise idle)
+                for (int t = kThreads - 1 - tid; t < keys; t += kThreads) {
                     const int j = row0 + t;
                     float a = (rd && j < n_eff) ? mass[(int64_t)u * n + j] : 0.f;     // tasks of earlier rounds
                     if (j < n_eff)
