@@ -8,19 +8,22 @@
 //          read in place and nothing is packed at all); fp32: V[T] transposed
 //          ([d][64 keys] tiles), so that both MFMA operands are contiguous fragments.
 //   flash  one workgroup = 128 kept queries of one query head (4 waves x 32
-//          rows).  K / V^T tiles of 64 keys are loaded straight into LDS
-//          (double buffered, one barrier per tile) and shared by the four waves;
-//          the S^T product of the next tile overlaps the softmax of the current.
-//          S^T = K Q^T and O^T = V^T P^T are taken on 32x32 MFMA tiles, so a
-//          lane owns one query column: the online-softmax statistics are
-//          per-lane scalars and only the running maximum crosses lanes (one
-//          register swap between the two half-waves per tile).  The steady-state
-//          step is one basic block with an explicit instruction schedule: LDS
-//          operand reads run ahead of the MFMA that consumes them, the vector
-//          work is spread between the MFMAs, and the direct-to-LDS loads of the
-//          coming tiles are issued one at a time in its first half.  Causality is
-//          the plain lower triangle in kept-token coordinates because T is
-//          ascending.  Query rows are gathered by idx on load, output rows are
+//          rows).  K / V tiles of 64 keys are loaded straight into LDS (double
+//          buffered) and shared by the four waves.  S^T = K Q^T and O^T = V^T P^T
+//          are taken on 32x32 MFMA tiles, so a lane owns one query column and the
+//          softmax statistics are per-lane scalars.  The key loop is a pipeline
+//          three tiles deep: a step multiplies P.V for tile t-1, takes the
+//          exponentials of tile t and multiplies K Q^T for tile t+1, with the
+//          instruction order of the steady state written out (operand reads a few
+//          matrix instructions ahead, the vector work and the tile requests spread
+//          between them); every tile has a whole step to arrive from memory.
+//          The first pass over the keys uses no exponent offset at all (no running
+//          maximum, no exchange between lanes, no rescaling): exp2 of the scaled
+//          logits as they are.  That is exact as long as the row sums stay far
+//          inside the fp32 range, which is checked at the end; a workgroup with a
+//          row outside [2^-64, 2^64] repeats its tiles with running maxima.
+//          Causality is the plain lower triangle in kept-token coordinates because
+//          T is ascending.  Query rows are gathered by idx on load, output rows are
 //          scattered by idx on store.  The zero rows of dropped tokens are written
 //          by extra workgroups at the end of the same grid (one per head and span
 //          of positions), which run in the slots the thinning end of the
@@ -31,6 +34,7 @@
 // workgroup (all k keys) lasts a large part of the whole launch.
 #include <algorithm>
 #include <atomic>
+#include <type_traits>
 
 #include "launch.h"
 #include "ldsload.h"
@@ -45,8 +49,8 @@ constexpr int kFlashWavesBf16 = 4;
 constexpr int kFlashBlocksBf16 = 1;
 constexpr int kFillSpan = 512;       // positions per workgroup that clears dropped output rows
 constexpr float kLazyLog2 = 8.f;     // slack of the running softmax offset below the running maximum (log2 domain)
+constexpr float kSumLow = 0x1p-64f, kSumHigh = 0x1p64f;   // row sums of the offset-free pass that need no second pass
 constexpr int kSchedAhead = 3;       // LDS operand reads in flight ahead of the consuming MFMA
-constexpr int kSchedValu = 4;        // vector instructions placed between two MFMAs
 
 // NW = waves per workgroup, QB = 32-query blocks per wave: a workgroup covers 32 QB NW kept queries, its
 // K / V^T tiles are fetched from L2 once per that many queries, and every LDS operand fragment a wave
@@ -58,8 +62,8 @@ struct AttnCfg {
     static constexpr int NT = 64 * NW;                       // threads per workgroup
     static constexpr int CH = D / Elem<T>::kPerChunk;       // Q/K fragments per row per lane
     static constexpr int ODB = D / 32;                       // 32-row blocks of O^T
-    // LDS tiles are unpadded; the 16-byte chunks of a row are XOR-swizzled with (row & 7) instead, so
-    // that any 8 consecutive rows read at the same logical chunk hit 8 different bank groups.
+    // LDS tiles are unpadded; the 16-byte chunks of a row are XOR-swizzled with the row index instead, so
+    // that 16 consecutive rows read at the same logical chunk hit 16 different bank groups.
     static constexpr int KRB = D * E;                        // bytes per K row
     // bf16: V tiles stay row-major ([64 keys][d], like K) and the P.V operand is fetched with the LDS
     // transposing read; fp32 (no such read for 32-bit elements): V^T tiles ([d][64 keys]) packed beforehand.
@@ -125,12 +129,7 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
 // One tile (TILE_BYTES contiguous in global memory) -> one LDS buffer, without passing through
 // registers: every wave issues NLD loads of 1 KiB, lane L of a load writes LDS bytes [16 L, 16 L + 16)
 // of that KiB, and picks the global chunk that belongs there under the row swizzle.
-template <int NW, int NLD>
-__device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w, const int (&off)[NLD]) {
-    const unsigned lbase = lds_address(lbuf);
-#pragma unroll
-    for (int q = 0; q < NLD; ++q) load_kib_to_lds(gtile, off[q], lbase + (q * NW + w) * 1024);
-}
+
 
 // per-lane source offsets for tile_to_lds (rows of RB bytes)
 // Row swizzle of a row-major bf16 V tile (rows of RB bytes): the transposing read of a 16-lane group
@@ -139,14 +138,44 @@ __device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w
 template <int RB>
 __device__ __forceinline__ int v_row_swizzle(int row) { return ((row & 3) >> (RB == 128 ? 1 : 0)) << 2; }
 
+// Row swizzle of a tile whose rows are read 32 at a time at one logical chunk (K, and V^T for fp32): the LDS
+// serves a 16-byte-per-lane read 16 lanes per clock from 64 banks (256 bytes), so 16 consecutive rows must
+// land on 16 different chunks of that period: rows of 256 bytes or more XOR the chunk index with (row & 15),
+// rows of 128 bytes (two to a period, already apart by half of it) with ((row >> 1) & 7).
+template <int RB>
+__device__ __forceinline__ int k_row_swizzle(int row) { return RB >= 256 ? (row & 15) : ((row >> 1) & 7); }
+
 template <int RB, int NW, int NLD, bool VSWZ = false>
 __device__ __forceinline__ void lds_fill_offsets(int w, int lane, int (&off)[NLD]) {
 #pragma unroll
     for (int q = 0; q < NLD; ++q) {
         const int o = (q * NW + w) * 1024 + lane * 16;
         const int r = o / RB, p = (o % RB) >> 4;
-        off[q] = r * RB + ((p ^ (VSWZ ? v_row_swizzle<RB>(r) : (r & 7))) << 4);
+        off[q] = r * RB + ((p ^ (VSWZ ? v_row_swizzle<RB>(r) : k_row_swizzle<RB>(r))) << 4);
     }
+}
+
+// Load q of a tile (see tile_to_lds).  When the NW KiB that the waves fetch together cover a whole number of
+// swizzle periods (16 rows), a lane's offset inside every such group is the same: one register serves all
+// loads and the group's offset goes into the scalar base address.
+template <int RB, int NW> constexpr bool kOffsetsRepeat = (NW * 1024 / RB) % 16 == 0;
+
+template <int RB, int NW, int NLD>
+__device__ __forceinline__ void tile_load(const char* gtile, int q, const int (&off)[NLD], unsigned lds_dst) {
+    if constexpr (kOffsetsRepeat<RB, NW>) load_kib_to_lds(gtile + q * NW * 1024, off[0], lds_dst);
+    else load_kib_to_lds(gtile, off[q], lds_dst);
+}
+template <int RB, int NW, int NLD>
+__device__ __forceinline__ void tile_load_pinned(const char* gtile, int q, const int (&off)[NLD], unsigned lds_dst, unsigned& pin) {
+    if constexpr (kOffsetsRepeat<RB, NW>) load_kib_to_lds_pinned(gtile + q * NW * 1024, off[0], lds_dst, pin);
+    else load_kib_to_lds_pinned(gtile, off[q], lds_dst, pin);
+}
+
+template <int RB, int NW, int NLD>
+__device__ __forceinline__ void tile_to_lds(const char* gtile, char* lbuf, int w, const int (&off)[NLD]) {
+    const unsigned lbase = lds_address(lbuf);
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) tile_load<RB, NW, NLD>(gtile, q, off, lbase + (q * NW + w) * 1024);
 }
 
 // S^T = K Q^T for 32 keys (block blk of the 64-key tile in LDS buffer kb) and the wave's QB query blocks:
@@ -218,7 +247,7 @@ template <int D, int NW, int QB> struct PV<float, D, NW, QB> {
     }
     template <int HALF>
     __device__ static __forceinline__ void run(const char* vb, const int (&lane_off)[C::ODB], const Probs& p, floatx16 (&o)[QB][C::ODB]) {
-        const int i = lane_off[0], h = lane_off[1], sw = i & 7;
+        const int i = lane_off[0], h = lane_off[1], sw = k_row_swizzle<C::VRB>(i);
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             // step (a, t): this lane contributes key 32*HALF + 8*a + 4*h + t
@@ -235,30 +264,6 @@ template <int D, int NW, int QB> struct PV<float, D, NW, QB> {
         }
     }
 };
-
-// Instruction order of the steady-state step (one basic block: S^T of the next tile, exponentials and
-// P.V of the current one): LDS operand reads run a few fragments ahead of the matrix instructions that
-// consume them and the vector work is spread evenly between the matrix instructions, so that a wave
-// neither waits on LDS latency in front of every MFMA nor bunches its vector work.
-template <typename T, int D, int QB>
-__device__ __forceinline__ void flash_schedule() {
-    if constexpr (Elem<T>::kBytes == 2 && D == 128) {
-#pragma unroll
-        for (int q = 0; q < kSchedAhead; ++q) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-#pragma unroll
-        for (int q = 0; q < 13; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                       // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                        // LDS read
-            __builtin_amdgcn_sched_group_barrier(0x002, kSchedValu * QB, 0);          // vector ALU
-        }
-#pragma unroll
-        for (int q = 13; q < 32; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                       // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                        // LDS reads: two per P.V operand
-            __builtin_amdgcn_sched_group_barrier(0x002, kSchedValu * QB, 0);          // vector ALU
-        }
-    }
-}
 
 // The two half-waves (lanes l and l ^ 32) hold the two halves of each query's keys: combine a per-lane
 // value across them with one register swap (no trip through LDS).
@@ -357,13 +362,6 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     }
     floatx16 o[QB][C::ODB];
     float m_run[QB], l_run[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
-#pragma unroll
-        for (int db = 0; db < C::ODB; ++db) o[qb][db] = floatx16{0};
-    }
 
     const int ntiles = (min(i0 + kBM, kk) + kBN - 1) / kBN;
     const int wave_first_row = i0 + kRW * w, wave_last_row = wave_first_row + kRW - 1;
@@ -372,180 +370,314 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     const char* vg = reinterpret_cast<const char*>(Vp + b * vp0 + g * vp1);   // V tiles of this unit (V^T tiles for fp32)
     char* const Kb0 = smem;
     char* const Vb0 = smem + 2 * C::TILE_BYTES;
-    const int sw = i & 7;
+    const int sw = k_row_swizzle<C::KRB>(i);
     int koff[C::NLD], voff[C::NLD];
     lds_fill_offsets<C::KRB, NW, C::NLD>(w, lane, koff);
     lds_fill_offsets<C::VRB, NW, C::NLD, C::VROWS>(w, lane, voff);
     int vlane[C::ODB];
     PV<T, D, NW, QB>::lane_offsets(lane, vlane);
 
-    // Software pipeline over key tiles.  While tile t is in its softmax (vector ALU) and P.V (matrix)
-    // stages, the S^T product of tile t+1 already runs on the matrix cores and the loads of K tile t+2
-    // and V^T tile t+1 are in flight straight into LDS.  One barrier per tile.
-    tile_to_lds<NW, C::NLD>(kg, Kb0, w, koff);
-    tile_to_lds<NW, C::NLD>(vg, Vb0, w, voff);
-    if (ntiles > 1) tile_to_lds<NW, C::NLD>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
+    const unsigned klds = lds_address(Kb0) + w * 1024, vlds = lds_address(Vb0) + w * 1024;
+    // One pass over the key tiles.  SAFE = false: the exponent offset stays 0 (softmax is shift invariant, and
+    // floating point keeps its relative precision at any magnitude), so there is no running maximum, no
+    // exchange between lanes and no rescaling in the loop; valid as long as the row sums stay far inside the
+    // fp32 range, which is checked afterwards.  SAFE = true: the offset follows the running maximum.
+    auto pass = [&](auto safe_tag) {
+    constexpr bool SAFE = decltype(safe_tag)::value;
+    using Probs = typename PV<T, D, NW, QB>::Probs;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < C::ODB; ++db) o[qb][db] = floatx16{0};
+    }
+    // Software pipeline over key tiles, three stages deep.  Step t runs, on the matrix cores, P.V of tile
+    // t-1 (first half) and the S^T product of tile t+1 (second half), and on the vector ALU the
+    // exponentials of tile t: the three work on different tiles, so nothing inside a step waits for
+    // anything else inside it.  K tile t+2 is requested in the first half of step t and first read in the
+    // second half of step t+1; V tile t+1 is requested in the second half of step t and first read at the
+    // start of step t+2: every tile has a whole step to arrive.  Two barriers per step (middle and end),
+    // each preceded by a wait that leaves this wave's two most recent tile requests outstanding.
+    tile_to_lds<C::KRB, NW, C::NLD>(kg, Kb0, w, koff);
+    tile_to_lds<C::VRB, NW, C::NLD>(vg, Vb0, w, voff);
+    if (ntiles > 1) tile_to_lds<C::KRB, NW, C::NLD>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     floatx16 sa[QB][2], sb[QB][2];
+    Probs pa, pb;
     qk_block<T, D, NW, QB>(Kb0, 0, i, h, sw, qf, sa);       // tile 0 is visible to every row
     qk_block<T, D, NW, QB>(Kb0, 1, i, h, sw, qf, sa);
-    const unsigned klds = lds_address(Kb0) + w * 1024, vlds = lds_address(Vb0) + w * 1024;
+    __syncthreads();                                         // step 0 overwrites K tile 0
 
-    auto step = [&](int t, floatx16 (&sc)[QB][2], floatx16 (&sn)[QB][2]) {
-        // This step's loads: K tile t+2 into the buffer tile t has left, V^T tile t+1 into the one tile t-1
-        // has left.  In the steady state they are issued one at a time, spread over the step by tying
-        // each to one of the exponentials (a burst of them stalls every wave of the workgroup at the
-        // address unit right after the barrier); elsewhere in one go.  Past the last tile the last
-        // tile is fetched again, unread.
+    // wait until at most `pending` of this wave's tile requests (NLD loads each) are outstanding, and for its LDS reads
+    auto wait_tiles = [&](int pending) {
+        if (pending >= 2) __builtin_amdgcn_s_waitcnt(0x0070 | ((2 * C::NLD) & 15) | (((2 * C::NLD) >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0070);
+    };
+    // bf16, one query block per wave: the two halves of a steady-state step with the instruction order written
+    // out.  Every matrix instruction is followed by its share of the half's vector work (16 pieces: two
+    // products, two exponentials, a pack and a row-sum update per pair of keys) and preceded by the LDS reads
+    // of the operand kSchedAhead matrix instructions ahead; nothing moves across the fences between them.
+    // HALF 0: P.V of the previous tile (src = its V tile), exponentials of key block 0, requests for a K tile.
+    // HALF 1: S^T of the next tile (src = its K tile), exponentials of key block 1, requests for a V tile.
+    constexpr bool kExplicit = Elem<T>::kBytes == 2 && QB == 1;
+    auto steady_half = [&](auto half_tag, const char* src, floatx16 (&sc)[QB][2], floatx16 (&sn)[QB][2], Probs& pp, Probs& pc,
+                           float (&sum)[QB], const char* gt, unsigned lt) {
+        if constexpr (kExplicit) {
+        constexpr int HALF = decltype(half_tag)::value;
+        constexpr int NM = HALF == 0 ? 4 * C::ODB : 2 * C::CH;     // matrix instructions of the half
+        constexpr int PPM = 16 / NM;                                // vector pieces per matrix instruction
+        typedef short shortx4 __attribute__((ext_vector_type(4)));
+        using lds_ptr = __attribute__((address_space(3))) shortx4*;
+        uintx4 frag[NM];
+        float pe[16];
+        auto read = [&](int j) {
+            if constexpr (HALF == 0) {
+                const int hf = j / (2 * C::ODB), s2 = (j / C::ODB) & 1, db = j % C::ODB;
+                const char* a0 = src + vlane[db] + (32 * hf + 16 * s2) * C::VRB;
+                const uintx2 lo = __builtin_bit_cast(uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)a0));
+                const uintx2 hi = __builtin_bit_cast(uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(a0 + 8 * C::VRB)));
+                frag[j] = uintx4{lo[0], lo[1], hi[0], hi[1]};
+            } else {
+                const int blk = j & 1, cc = j >> 1;
+                frag[j] = *reinterpret_cast<const uintx4*>(src + (blk * 32 + i) * C::KRB + swz_chunk(2 * cc + h, sw));
+            }
+        };
+        auto piece = [&](int q) {                                   // q = 0..15: half a pair of keys
+            const int r = 2 * (q >> 1);
+            if ((q & 1) == 0) {
+                pe[r] = sc[0][HALF][r] * c;
+                pe[r + 1] = sc[0][HALF][r + 1] * c;
+                pe[r] = fast_exp2(pe[r]);
+            } else {
+                pe[r + 1] = fast_exp2(pe[r + 1]);
+#pragma unroll
+                for (int L = 0; L < C::NLD; ++L)
+                    if (q == ((2 * L + 1) * 16) / (2 * C::NLD) + 1) {          // request L rides on this piece
+                        unsigned pin = __float_as_uint(pe[r + 1]);
+                        if constexpr (HALF == 0) tile_load_pinned<C::KRB, NW, C::NLD>(gt, L, koff, lt + L * NW * 1024, pin);
+                        else tile_load_pinned<C::VRB, NW, C::NLD>(gt, L, voff, lt + L * NW * 1024, pin);
+                        pe[r + 1] = __uint_as_float(pin);
+                    }
+                const uint32_t pk = pack_bf16x2(pe[r], pe[r + 1]);
+                pc[0][HALF][r >> 3][(r & 7) >> 1] = pk;
+                sum[0] = add_bf16x2(pk, sum[0]);
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < kSchedAhead; ++j) read(j);
+#pragma unroll
+        for (int j = 0; j < NM; ++j) {
+            if (j + kSchedAhead < NM) read(j + kSchedAhead);
+            if constexpr (HALF == 0) {
+                const int hf = j / (2 * C::ODB), s2 = (j / C::ODB) & 1, db = j % C::ODB;
+                o[0][db] = mma_frag<__bf16>(frag[j], pp[0][hf][s2], o[0][db]);
+            } else {
+                const int blk = j & 1, cc = j >> 1;
+                sn[0][blk] = mma_frag<__bf16>(frag[j], qf[0][cc], cc == 0 ? floatx16{0} : sn[0][blk]);
+            }
+#pragma unroll
+            for (int q = 0; q < PPM; ++q) piece(j * PPM + q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        }
+    };
+    auto step = [&](int t, floatx16 (&sc)[QB][2], floatx16 (&sn)[QB][2], Probs& pp, Probs& pc) {
+        // requests of this step: K tile t+2 into the buffer tile t has left (first half), V tile t+1 into the
+        // one tile t-1 leaves at the middle barrier (second half).  In the steady state they are issued one
+        // at a time, each tied to one exponential (a burst of them stalls every wave of the workgroup at the
+        // address unit); elsewhere in one go.  Past the last tile the last tile is fetched again, unread.
         const char* kgt = kg + (int64_t)min(t + 2, ntiles - 1) * C::TILE_BYTES;
         const char* vgt = vg + (int64_t)min(t + 1, ntiles - 1) * C::TILE_BYTES;
         const unsigned kl = klds + (t & 1) * C::TILE_BYTES, vl = vlds + ((t + 1) & 1) * C::TILE_BYTES;
-        auto fetch_all = [&]() {
+        auto fetch_k = [&]() {
 #pragma unroll
-            for (int q = 0; q < C::NLD; ++q) load_kib_to_lds(kgt, koff[q], kl + q * NW * 1024);
-#pragma unroll
-            for (int q = 0; q < C::NLD; ++q) load_kib_to_lds(vgt, voff[q], vl + q * NW * 1024);
+            for (int q = 0; q < C::NLD; ++q) tile_load<C::KRB, NW, C::NLD>(kgt, q, koff, kl + q * NW * 1024);
         };
-        // the step's 2 NLD loads ride on the 16 exponentials of key block 0 (the first half of the step, so
-        // that they have the second half to land): load L after exponential (2L+1) * 16 / (4 NLD)
-        auto fetch_after_exp = [&](int blk, int r, float& pinned) {
-            if (blk != 0) return;
+        auto fetch_v = [&]() {
 #pragma unroll
-            for (int L = 0; L < 2 * C::NLD; ++L)
-                if (r == ((2 * L + 1) * 16) / (4 * C::NLD)) {
+            for (int q = 0; q < C::NLD; ++q) tile_load<C::VRB, NW, C::NLD>(vgt, q, voff, vl + q * NW * 1024);
+        };
+        // load L of a half rides on exponential (2L+1) * 16 / (2 NLD) of that half's key block
+        auto fetch_after_exp = [&](int blk, int r, float& pinned) {
+#pragma unroll
+            for (int L = 0; L < C::NLD; ++L)
+                if (r == ((2 * L + 1) * 16) / (2 * C::NLD)) {
                     unsigned pin = __float_as_uint(pinned);
-                    if (L < C::NLD) load_kib_to_lds_pinned(kgt, koff[L], kl + L * NW * 1024, pin);
-                    else load_kib_to_lds_pinned(vgt, voff[L - C::NLD], vl + (L - C::NLD) * NW * 1024, pin);
+                    if (blk == 0) tile_load_pinned<C::KRB, NW, C::NLD>(kgt, L, koff, kl + L * NW * 1024, pin);
+                    else tile_load_pinned<C::VRB, NW, C::NLD>(vgt, L, voff, vl + L * NW * 1024, pin);
                     pinned = __uint_as_float(pin);
                 }
         };
-        if (C::VROWS && v_in_place && (t + 1) * kBN > kk) {
+        const bool has_pv = t >= 1 && t - 1 < my_tiles, has_s = t < my_tiles, has_next = t + 1 < my_tiles;
+        const char* kb = Kb0 + ((t + 1) & 1) * C::TILE_BYTES;
+        const char* vb = Vb0 + ((t + 1) & 1) * C::TILE_BYTES;          // V tile t-1
+        if (C::VROWS && v_in_place && t >= 1 && t * kBN > kk) {
             // A V tile read in place from the evicted cache may hold anything in its rows past k; their
             // probabilities are exact zeros, but 0 * NaN is not: clear those rows in LDS (last tile only).
-            char* vt = Vb0 + (t & 1) * C::TILE_BYTES;
+            char* vt = Vb0 + ((t + 1) & 1) * C::TILE_BYTES;
             const uintx4 z = {0, 0, 0, 0};
-            for (int q = tid + (kk - t * kBN) * (C::VRB / 16); q < kBN * (C::VRB / 16); q += kNT) store16(vt + q * 16, z);
+            for (int q = tid + (kk - (t - 1) * kBN) * (C::VRB / 16); q < kBN * (C::VRB / 16); q += kNT) store16(vt + q * 16, z);
             __syncthreads();
         }
-        if (t < my_tiles) {
-            const int t0 = t * kBN;
-            const char* kb = Kb0 + ((t + 1) & 1) * C::TILE_BYTES;
-            const char* vb = Vb0 + (t & 1) * C::TILE_BYTES;
-            if (t0 + kBN - 1 > wave_first_row) {             // tile touches the diagonal (wave-uniform)
+        float mc[QB], sum[QB];
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
+        for (int qb = 0; qb < QB; ++qb) { mc[qb] = 0.f; sum[qb] = 0.f; }
+        if (has_s && t * kBN + kBN - 1 > wave_first_row) {       // tile touches the diagonal (wave-uniform)
 #pragma unroll
-                    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (t0 + 32 * blk + acc_row(r, h) > qrow[qb]) sc[qb][blk][r] = -INFINITY;
-            }
-            // raw-logit maxima; the softmax scale (c > 0, log2 domain) is folded into the exponent
-            float m_new[QB], mc[QB];
-            const float lazy = kLazyLog2 / c;
-            bool moved = false;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float mx = -INFINITY;
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                 for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[qb][blk][r]);
-                mx = xhalf_max(mx);
-                // The exponent offset follows the maximum lazily: it moves only when a logit exceeds it by
-                // more than kLazyLog2 in the log2 domain, so probabilities stay below 2^kLazyLog2 (exact in
-                // exact arithmetic: softmax is shift invariant) and the accumulators are rescaled rarely.
-                // The first tile always moves it (offset -inf; key 0 is visible to every row, so mx is finite).
-                const bool grow = mx > m_run[qb] + lazy;
-                m_new[qb] = grow ? mx : m_run[qb];
-                mc[qb] = m_new[qb] * c;
-                moved |= grow;
-            }
-            if (__any(moved)) {                              // rescale only when some row's offset moved
+                    for (int r = 0; r < 16; ++r)
+                        if (t * kBN + 32 * blk + acc_row(r, h) > qrow[qb]) sc[qb][blk][r] = -INFINITY;
+        }
+        // Probabilities of this tile.  bf16: packed once into P^T operand fragments, and the row sums are
+        // taken over the values as rounded to bf16, so that numerator and denominator of the output use
+        // the same weights.  fp32: in place.
+        auto exps = [&](int blk, bool spread_loads) {
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    const float alpha = fast_exp2(m_run[qb] * c - mc[qb]);   // 1 where the maximum stayed
-                    l_run[qb] *= alpha;
+            for (int qb = 0; qb < QB; ++qb) {
+                if constexpr (Elem<T>::kBytes == 2) {
 #pragma unroll
-                    for (int db = 0; db < C::ODB; ++db)
+                    for (int r = 0; r < 16; r += 2) {
+                        float p0 = fast_exp2(SAFE ? fmaf(sc[qb][blk][r], c, -mc[qb]) : sc[qb][blk][r] * c);
+                        float p1 = fast_exp2(SAFE ? fmaf(sc[qb][blk][r + 1], c, -mc[qb]) : sc[qb][blk][r + 1] * c);
+                        if (spread_loads && qb == 0) { fetch_after_exp(blk, r, p0); fetch_after_exp(blk, r + 1, p1); }
+                        const uint32_t pk = pack_bf16x2(p0, p1);
+                        pc[qb][blk][r >> 3][(r & 7) >> 1] = pk;
+                        sum[qb] = add_bf16x2(pk, sum[qb]);
+                    }
+                } else {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
-                    m_run[qb] = m_new[qb];
+                    for (int r = 0; r < 16; ++r) {
+                        float p = fast_exp2(SAFE ? fmaf(sc[qb][blk][r], c, -mc[qb]) : sc[qb][blk][r] * c);
+                        if (spread_loads && qb == 0) fetch_after_exp(blk, r, p);
+                        pc[qb][blk][r] = p;
+                        sum[qb] += p;
+                    }
                 }
             }
-            // Probabilities of this tile.  bf16: packed once into P^T operand fragments, and the row sums are
-            // taken over the values as rounded to bf16, so that numerator and denominator of the output use
-            // the same weights.  fp32: in place.
-            float sum[QB];
+        };
+        const bool steady = has_pv && has_next && !SAFE;
+        // ---- first half: P.V of tile t-1 | exponentials of key block 0 of tile t | requests for K tile t+2
+        if (steady) {
+            if constexpr (kExplicit) steady_half(std::integral_constant<int, 0>{}, vb, sc, sn, pp, pc, sum, kgt, kl);
+            else {
+                exps(0, true);
+                PV<T, D, NW, QB>::template run<0>(vb, vlane, pp, o);
+                PV<T, D, NW, QB>::template run<1>(vb, vlane, pp, o);
+            }
+        } else {
+            fetch_k();
+            if (has_pv) {
+                PV<T, D, NW, QB>::template run<0>(vb, vlane, pp, o);
+                PV<T, D, NW, QB>::template run<1>(vb, vlane, pp, o);
+            }
+            if (has_s) {
+                if constexpr (SAFE) {
+                    // raw-logit maxima; the softmax scale (c > 0, log2 domain) is folded into the exponent.  The
+                    // offset follows the maximum lazily: it moves only when a logit exceeds it by more than
+                    // kLazyLog2 in the log2 domain, so probabilities stay below 2^kLazyLog2 and the accumulators
+                    // (which hold every tile up to t-1 by now) are rescaled rarely.  The first tile always moves
+                    // it (offset -inf; key 0 is visible to every row, so the maximum is finite).
+                    const float lazy = kLazyLog2 / c;
+                    float m_new[QB];
+                    bool moved = false;
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) sum[qb] = 0.f;
-            typename PV<T, D, NW, QB>::Probs pr;
-            auto exps = [&](int blk, bool spread_loads) {
+                    for (int qb = 0; qb < QB; ++qb) {
+                        float mx = -INFINITY;
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb) {
-                    if constexpr (Elem<T>::kBytes == 2) {
+                        for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-                        for (int r = 0; r < 16; r += 2) {
-                            float p0 = fast_exp2(fmaf(sc[qb][blk][r], c, -mc[qb]));
-                            float p1 = fast_exp2(fmaf(sc[qb][blk][r + 1], c, -mc[qb]));
-                            if (spread_loads && qb == 0) { fetch_after_exp(blk, r, p0); fetch_after_exp(blk, r + 1, p1); }
-                            const uint32_t pk = pack_bf16x2(p0, p1);
-                            pr[qb][blk][r >> 3][(r & 7) >> 1] = pk;
-                            sum[qb] = add_bf16x2(pk, sum[qb]);
-                        }
-                    } else {
+                            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[qb][blk][r]);
+                        mx = xhalf_max(mx);
+                        const bool grow = mx > m_run[qb] + lazy;
+                        m_new[qb] = grow ? mx : m_run[qb];
+                        mc[qb] = m_new[qb] * c;
+                        moved |= grow;
+                    }
+                    if (__any(moved)) {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            float p = fast_exp2(fmaf(sc[qb][blk][r], c, -mc[qb]));
-                            if (spread_loads && qb == 0) fetch_after_exp(blk, r, p);
-                            pr[qb][blk][r] = p;
-                            sum[qb] += p;
+                        for (int qb = 0; qb < QB; ++qb) {
+                            const float alpha = fast_exp2(m_run[qb] * c - mc[qb]);   // 1 where the maximum stayed
+                            l_run[qb] *= alpha;
+#pragma unroll
+                            for (int db = 0; db < C::ODB; ++db)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+                            m_run[qb] = m_new[qb];
                         }
                     }
                 }
-            };
-            if (t + 1 < my_tiles) {
-                // matrix stream: S^T of tile t+1, then P.V of tile t; vector stream: exponentials of tile t
+                exps(0, false);
+            }
+        }
+        wait_tiles(2);                                        // K tile t+1 has landed (this wave's part)
+        __syncthreads();
+        // ---- second half: S^T of tile t+1 | exponentials of key block 1 of tile t | requests for V tile t+1
+        if (steady) {
+            if constexpr (kExplicit) steady_half(std::integral_constant<int, 1>{}, kb, sc, sn, pp, pc, sum, vgt, vl);
+            else {
+                exps(1, true);
                 qk_block<T, D, NW, QB>(kb, 0, i, h, sw, qf, sn);
                 qk_block<T, D, NW, QB>(kb, 1, i, h, sw, qf, sn);
-                exps(0, true);
-                PV<T, D, NW, QB>::template run<0>(vb, vlane, pr, o);
-                exps(1, true);
-                PV<T, D, NW, QB>::template run<1>(vb, vlane, pr, o);
-                flash_schedule<T, D, QB>();
-            } else {
-                fetch_all();
-                exps(0, false);
-                PV<T, D, NW, QB>::template run<0>(vb, vlane, pr, o);
-                exps(1, false);
-                PV<T, D, NW, QB>::template run<1>(vb, vlane, pr, o);
             }
+        } else {
+            fetch_v();
+            if (has_next) {
+                qk_block<T, D, NW, QB>(kb, 0, i, h, sw, qf, sn);
+                qk_block<T, D, NW, QB>(kb, 1, i, h, sw, qf, sn);
+            }
+            if (has_s) exps(1, false);
+        }
+        if (has_s) {
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) l_run[qb] += sum[qb];
-        } else {
-            fetch_all();
         }
-        __builtin_amdgcn_s_waitcnt(0);                       // this wave's direct-to-LDS loads have landed
+        wait_tiles(2);                                        // V tile t has landed (this wave's part)
         __syncthreads();
     };
-    for (int t = 0; t < ntiles; t += 2) {
-        step(t, sa, sb);
-        if (t + 1 < ntiles) step(t + 1, sb, sa);
+    // steps 0 .. ntiles: the last one only finishes P.V of the last tile
+    for (int t = 0; t <= ntiles; t += 2) {
+        step(t, sa, sb, pb, pa);
+        if (t + 1 <= ntiles) step(t + 1, sb, sa, pa, pb);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    };
+    pass(std::false_type{});
+    {
+        // the offset-free pass stands if every row sum of the workgroup is finite and far from both ends of the
+        // fp32 range (no exponential overflowed, the dominant terms did not underflow); otherwise the whole
+        // workgroup repeats its tiles with running maxima
+        bool bad = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float l_tot = xhalf_sum(l_run[qb]);
+            bad |= qrow[qb] < kk && !(l_tot >= kSumLow && l_tot <= kSumHigh);   // rows past k are never stored
+        }
+        if (__syncthreads_or(bad)) pass(std::true_type{});
     }
 
+    // Output rows.  Everything the stores need is derived again from the thread index here (the empty asm
+    // keeps the compiler from carrying row numbers and pointers through the key loop, where registers are scarce).
+    int tid_out = threadIdx.x;
+    asm volatile("" : "+v"(tid_out));
+    const int w_out = tid_out >> 6, i_out = tid_out & 31, h_out = (tid_out >> 5) & 1;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float l_tot = xhalf_sum(l_run[qb]);
-        if (qrow[qb] < kk) {
+        const int qr = i0 + kRW * w_out + 32 * qb + i_out;
+        if (qr < kk) {
             const float inv = 1.f / l_tot;
-            const int orow = out_compact ? qrow[qb] : qpos[qb];
+            const int orow = (out_compact || !tidx) ? qr : tidx[qr];
             T* op = O + ((int64_t)bh * n + orow) * D;
 #pragma unroll
             for (int db = 0; db < C::ODB; ++db)
 #pragma unroll
                 for (int a = 0; a < 4; ++a)
-                    store_out4<T>(op + 32 * db + 8 * a + 4 * h, o[qb][db][4 * a] * inv, o[qb][db][4 * a + 1] * inv,
+                    store_out4<T>(op + 32 * db + 8 * a + 4 * h_out, o[qb][db][4 * a] * inv, o[qb][db][4 * a + 1] * inv,
                                   o[qb][db][4 * a + 2] * inv, o[qb][db][4 * a + 3] * inv);
         }
     }

@@ -248,9 +248,13 @@ def test_scores_match_oracle(case):
 
 
 # ------------------------------------------------------------------ attention
-def _attention_case(B, Hq, Hkv, n, d, dtype, ks, seed=0, flags=0, dense=False):
+def _attention_case(B, Hq, Hkv, n, d, dtype, ks, seed=0, flags=0, dense=False, reshape_inputs=None):
     G = Hq // Hkv
     w = make_custom(B, Hq, Hkv, n, d, dtype, seed=seed)
+    if reshape_inputs is not None:                 # (Q, K) -> (Q', K'), rounded back to the storage type
+        q2, k2 = reshape_inputs(w.Q, w.K)
+        rnd = (lambda x: torch.from_numpy(x).bfloat16().float().numpy()) if dtype == "bf16" else (lambda x: x.astype(np.float32))
+        w.Q, w.K = rnd(np.ascontiguousarray(q2, dtype=np.float32)), rnd(np.ascontiguousarray(k2, dtype=np.float32))
     Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
     units = B * Hkv
     r = np.random.Generator(np.random.PCG64(seed + 1))
@@ -306,6 +310,24 @@ def test_attention_dense_mode_equals_dense_oracle():
     say("attention dense (idx=k=NULL)")
     _attention_case(1, 4, 2, 450, 128, "bf16", [450, 450], seed=5, dense=True)
     _attention_case(1, 2, 2, 200, 64, "f32", [200, 200], seed=6, dense=True)
+
+
+def test_attention_logits_far_from_zero():
+    """Rows whose logits leave the range in which exponentials need no offset (the kernel's first pass takes
+    exp2 of the scaled logits as they are and repeats a workgroup with running maxima when a row sum leaves
+    [2^-64, 2^64]): logits of +-150 and more, logits that are all near -100 or near +100, and a mix of ordinary
+    and extreme heads in one launch."""
+    say("attention with very large / very negative logits")
+    for dtype, d, seed, gain in (("bf16", 128, 31, 40.0), ("f32", 64, 32, 16.0)):   # fp32: +-60, within its 1e-4 bound
+        ks = [450, 257, 129, 450]
+        _attention_case(1, 4, 4, 450, d, dtype, ks, seed=seed, reshape_inputs=lambda q, k: (q * gain, k))
+        shift = 3.0 if d == 128 else 4.5
+        _attention_case(1, 4, 4, 450, d, dtype, ks, seed=seed + 2, reshape_inputs=lambda q, k: (q - shift, k + shift))
+        _attention_case(1, 4, 4, 450, d, dtype, ks, seed=seed + 4, reshape_inputs=lambda q, k: (q + shift, k + shift))
+        def mixed(q, k):
+            q = q.copy(); q[:, 1] *= gain; q[:, 2] -= shift; k = k.copy(); k[:, 2] += shift
+            return q, k
+        _attention_case(1, 4, 4, 450, d, dtype, ks, seed=seed + 6, reshape_inputs=mixed)
 
 
 def test_attention_compact_output_rows():
