@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 MFMA_FP32_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0
+PREFILL_KERNELS = ("score_rowstats", "score_colsum", "select", "compact_kv", "pack_kv", "flash_kept")
 
 
 def read_traffic(kernel: str, workload: str):
@@ -158,6 +159,7 @@ def run_stack(args):
     Kt4, Vt4 = Kt.view(B, H, n, d), Vt.view(B, H, n, d)
     ws_s = ws_p = None
     caches, fulls, quants, kept, layer_ms, samples = [], [], [], [], [], []
+    kern_us = {}
     sample_layers = {0, (L - 1) // 2, L - 1}
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for layer in range(L):
@@ -184,6 +186,14 @@ def run_stack(args):
         ev1.record()
         torch.cuda.synchronize()
         layer_ms.append(ev0.elapsed_time(ev1) / args.steps)
+        z.zipvl_timing_enable(True)                    # per-kernel times of this layer (library events), outside the timed region
+        one_layer(); one_layer()
+        torch.cuda.synchronize()
+        for name in PREFILL_KERNELS:
+            ms, cnt = z.zipvl_timing_read(z.KERNELS.index(name))
+            if cnt:
+                kern_us[name] = kern_us.get(name, 0.0) + 1e3 * ms / cnt
+        z.zipvl_timing_enable(False)
         k_h = k.cpu().numpy().astype(np.int64)
         kept.append(k_h / n)
         cap_c = int(k_h.max()) + steps_dec + 8
@@ -309,6 +319,7 @@ def run_stack(args):
                    "decode_steps": steps_dec},
         "kept_pct": 100.0 * float(kept.mean()), "kept_pct_first_last_layer": [100.0 * float(kept[0].mean()), 100.0 * float(kept[-1].mean())],
         "layer_ms_first_last": [layer_ms[0], layer_ms[-1]],
+        "prefill_kernels_avg_us": {name: v / L for name, v in kern_us.items()},
         "decode": res, "decode_speedup_evicted_vs_full": res["full"]["ms_per_step"] / res["evicted"]["ms_per_step"],
         "roofline": {"kernel": "decode_step_kernel (evicted caches)", "bound": "hbm", "achieved": res["evicted"]["GBps"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["evicted"]["GBps"] / HBM_PEAK_GBS,

@@ -332,7 +332,9 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
         const uintx4 z = {0, 0, 0, 0};
         char* base = reinterpret_cast<char*>(O + ((int64_t)fbh * n + p0) * D);
         for (int q = tid; q < (p1 - p0) * CPR; q += kNT)
-            if (!kept[q / CPR]) store16(base + (int64_t)q * 16, z);
+            // whole rows, written once and not read again by this path: streaming stores, so that they do not stay
+            // behind as dirty lines in the last-level cache, to be written back under the next kernel's reads
+            if (!kept[q / CPR]) __builtin_nontemporal_store(z, reinterpret_cast<uintx4*>(base + (int64_t)q * 16));
         return;
     }
     const int full = ug * ntq * G;                           // workgroups of a full group

@@ -29,15 +29,19 @@
 namespace zipvl {
 
 constexpr int kMaxGroup = 16;
-constexpr int kStageBytes = 32 * 1024;      // keys staged in LDS at once: 32 KiB / row bytes
+constexpr int kStageBufs = 4;               // stage buffers in LDS: three stages are in flight while one is worked on
 
-template <typename T, int D>
+// NWV waves per workgroup.  16 waves (one workgroup per CU): stages of 32 KiB; 8 waves (two per CU): 16 KiB;
+// never more than 128 keys (the column-sum buffers grow with the keys of a stage).
+template <typename T, int D, int NWV>
 struct ScoreCfg {
     static constexpr int E = Elem<T>::kBytes;
     static constexpr int CH = D / Elem<T>::kPerChunk;      // fragments per row per lane
     static constexpr int RB = D * E;                        // bytes per key row
-    static constexpr int SK = kStageBytes / RB;             // keys per stage
+    static constexpr int STG = NWV * 2048 < 128 * RB ? NWV * 2048 : 128 * RB;   // bytes per stage: two 1-KiB loads per wave, 128 keys at most
+    static constexpr int SK = STG / RB;                     // keys per stage
     static constexpr int KBS = SK / 32;                     // 32-key blocks per stage
+    static constexpr int NLD = STG / 1024 / NWV;            // 1-KiB loads per wave per stage
 };
 
 // The statistics (maximum m, exp-sum l relative to m, log2 domain scale c) of two disjoint key sets of one row.
@@ -58,11 +62,10 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
     ProbeList probes, int m, int NB, int n, int n_eff, float c, float2* __restrict__ partial, int nsplit, int bpc,
     float* __restrict__ mass, float* __restrict__ rank, int Hq, int Hkv, int kv_div)
 {
-    using C = ScoreCfg<T, D>;
-    constexpr int CH = C::CH, RB = C::RB, SK = C::SK, KBS = C::KBS;
-    constexpr int NLD = kStageBytes / 1024 / NWV;                    // 1-KiB loads per wave per stage
+    using C = ScoreCfg<T, D, NWV>;
+    constexpr int CH = C::CH, RB = C::RB, SK = C::SK, KBS = C::KBS, NLD = C::NLD, kStageBytes = C::STG;
     constexpr int kThreads = 64 * NWV;
-    extern __shared__ __attribute__((aligned(16))) char kstage[];   // two stage buffers
+    extern __shared__ __attribute__((aligned(16))) char kstage[];   // kStageBufs stage buffers
     __shared__ int sp[ZIPVL_MAX_PROBES];
     __shared__ float2 wstat[PASS == 1 ? NWV : 1][32];                // pass 1: per-wave row statistics
     __shared__ __attribute__((aligned(16))) float row_bias[PASS == 2 ? NWV : 1][32];
@@ -101,18 +104,26 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
         const int r = o / RB, p = (o % RB) >> 4;
         ld_off[q] = r * row_stride + ((p ^ (r & 7)) << 4);
     }
-    auto issue_stage = [&](int s, int buf) {
+    // Every wave issues exactly NLD loads per stage (pieces past the chunk's or the sequence's last row re-read
+    // the stage's first row and are never used), so that "all but the newest p stages have landed" is a count.
+    auto issue_stage = [&](int s) {
         const int row0 = (blk0 + s * KBS) * 32;
-        const int rows = min(blk1 * 32 - row0, SK);                  // rows of this stage that belong to the chunk
+        const int rows = min(min(blk1 * 32, n) - row0, SK);           // rows of this stage that exist and belong to the chunk
         const char* gbase = Ku + (int64_t)row0 * row_stride;
-        const int lim = n - 1 - row0;                                // rows past the last key re-read the stage's first row (masked later)
+        const unsigned dst = lds0 + (s % kStageBufs) * kStageBytes;
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
             const int r = ((q * NWV + w) * 1024 + lane * 16) / RB;
-            if (((q * NWV + w) * 1024) / RB < rows)                  // wave-uniform
-                load_kib_to_lds(gbase, r <= lim ? ld_off[q] : 0, lds0 + buf * kStageBytes + (q * NWV + w) * 1024);
+            load_kib_to_lds(gbase, r < rows ? ld_off[q] : 0, dst + (q * NWV + w) * 1024);
         }
     };
+    // wait until at most `pending` stages (NLD loads each) of this wave are still on their way
+    auto wait_stages = [&](int pending) {
+        if (pending >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NLD));
+        else if (pending == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | NLD);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+    };
+    static_assert(2 * NLD < 16, "vmcnt immediate");
 
 #pragma unroll 1
     for (int rd = 0; rd < rounds; ++rd) {
@@ -123,8 +134,9 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
         const int bh = b * Hq + g * G + head;
 
         if (rd) __syncthreads();                                     // the stage buffers of the previous round are free
-        issue_stage(0, 0);
-        if (S > 1) issue_stage(1, 1);
+#pragma unroll
+        for (int s = 0; s < kStageBufs - 1; ++s)
+            if (s < S) issue_stage(s);
 
         // this wave's probe rows: fragments of row nb*32 + i, held for the whole round
         uintx4 qf[CH];
@@ -157,12 +169,39 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
         }
 
         float m_run = -INFINITY, l_run = 0.f;                        // PASS 1
-        __builtin_amdgcn_s_waitcnt(0);                               // this wave's pieces of stages 0 and 1 have landed
-        __syncthreads();
+        // add the tasks' column sums of stage s (PASS 2) in task order and write the scores of its keys
+        // (taken by the workgroup's last threads first: with more waves than tasks those waves are otherwise idle)
+        auto reduce_stage = [&](int s) {
+            const int buf = s & 1;
+            const int row0 = (blk0 + s * KBS) * 32;
+            const int keys = min(min(blk1 * 32, n) - row0, SK);
+            for (int t = kThreads - 1 - tid; t < keys; t += kThreads) {
+                const int j = row0 + t;
+                float a = (rd && j < n_eff) ? mass[(int64_t)u * n + j] : 0.f;     // tasks of earlier rounds
+                if (j < n_eff)
+                    for (int q = 0; q < ntr; ++q) a += colbuf[buf][q][t];
+                if (rd + 1 < rounds) {
+                    mass[(int64_t)u * n + j] = a;
+                } else {
+                    a /= (float)G;
+                    int cnt = 0;
+                    if (j <= Pmin) cnt = m;
+                    else for (int q = 0; q < m; ++q) cnt += sp[q] >= j ? 1 : 0;
+                    mass[(int64_t)u * n + j] = a / (float)m;
+                    if (rank) rank[(int64_t)u * n + j] = cnt > 0 ? a / (float)cnt : 0.f;
+                }
+            }
+        };
 #pragma unroll 1
         for (int s = 0; s < S; ++s) {
-            const int buf = s & 1;
-            const char* kb0 = kstage + buf * kStageBytes;
+            // stage s has landed (this wave's pieces, then everyone's); everyone is done with stage s - 1, whose
+            // buffer takes stage s + kStageBufs - 1 and whose column sums are complete
+            wait_stages(min(kStageBufs - 2, S - 1 - s));
+            __syncthreads();
+            if (s + kStageBufs - 1 < S) issue_stage(s + kStageBufs - 1);
+            if (PASS == 2 && s > 0) reduce_stage(s - 1);
+            const int buf = s & 1;                                   // column-sum buffer of the stage
+            const char* kb0 = kstage + (s % kStageBufs) * kStageBytes;
             const int sblk = blk0 + s * KBS;                         // first key block of the stage
             if (active) {
 #pragma unroll 1
@@ -225,31 +264,10 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
                     }
                 }
             }
-            __builtin_amdgcn_s_waitcnt(0);                           // this wave's pieces of stage s + 1 have landed
-            __syncthreads();                                         // stage s is consumed, its column sums are in LDS
-            if (s + 2 < S) issue_stage(s + 2, buf);
-            if (PASS == 2) {
-                // add the tasks' sums of stage s in task order and write the scores of its keys
-                const int row0 = sblk * 32;
-                const int keys = min(min(blk1 * 32, n) - row0, SK);
-                // (taken by the workgroup's last threads first: with more waves than tasks those waves are otherwise idle)
-                for (int t = kThreads - 1 - tid; t < keys; t += kThreads) {
-                    const int j = row0 + t;
-                    float a = (rd && j < n_eff) ? mass[(int64_t)u * n + j] : 0.f;     // tasks of earlier rounds
-                    if (j < n_eff)
-                        for (int q = 0; q < ntr; ++q) a += colbuf[buf][q][t];
-                    if (rd + 1 < rounds) {
-                        mass[(int64_t)u * n + j] = a;
-                    } else {
-                        a /= (float)G;
-                        int cnt = 0;
-                        if (j <= Pmin) cnt = m;
-                        else for (int q = 0; q < m; ++q) cnt += sp[q] >= j ? 1 : 0;
-                        mass[(int64_t)u * n + j] = a / (float)m;
-                        if (rank) rank[(int64_t)u * n + j] = cnt > 0 ? a / (float)cnt : 0.f;
-                    }
-                }
-            }
+        }
+        if (PASS == 2) {
+            __syncthreads();                                         // the last stage's column sums are in LDS
+            reduce_stage(S - 1);
         }
 
         if (PASS == 1) {
@@ -302,11 +320,11 @@ template <typename T, int D, int NWV>
 static int launch_score_w(const void* Q, const void* K, const zipvl_dims& d, const ProbeList& pl, int m,
                           int n_eff, float scale, float* mass, float* rank, void* ws, int kv_div, hipStream_t st)
 {
-    using C = ScoreCfg<T, D>;
+    using C = ScoreCfg<T, D, NWV>;
     const float c = scale * kLog2e;
     float2* partial = (float2*)ws;
     const int units = d.B * d.Hkv, NB = probe_rows(m) / 32;
-    const size_t lds = 2 * kStageBytes;
+    const size_t lds = (size_t)kStageBufs * C::STG;
     static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&score_kernel<T, D, 1, NWV>),
@@ -319,7 +337,6 @@ static int launch_score_w(const void* Q, const void* K, const zipvl_dims& d, con
     const int slots = resident_slots(NWV);
     const int nblk1 = (n_eff + 31) / 32, bpc1 = blocks_per_chunk(nblk1, units, slots), nsplit = (nblk1 + bpc1 - 1) / bpc1;
     const int nblk2 = (d.n + 31) / 32, bpc2 = blocks_per_chunk(nblk2, units, slots), chunks2 = (nblk2 + bpc2 - 1) / bpc2;
-    (void)C::SK;
     {
         KernelTimer tm(ZIPVL_K_SCORE_ROWSTATS, st);
         hipLaunchKernelGGL((score_kernel<T, D, 1, NWV>), dim3(nsplit, units), dim3(64 * NWV), lds, st,
