@@ -138,13 +138,6 @@ __global__ __launch_bounds__(256) void pack_kv_kernel(
 template <int RB>
 __device__ __forceinline__ int v_row_swizzle(int row) { return ((row & 3) >> (RB == 128 ? 1 : 0)) << 2; }
 
-// Row swizzle of a tile whose rows are read 32 at a time at one logical chunk (K, and V^T for fp32): the LDS
-// serves a 16-byte-per-lane read 16 lanes per clock from 64 banks (256 bytes), so 16 consecutive rows must
-// land on 16 different chunks of that period: rows of 256 bytes or more XOR the chunk index with (row & 15),
-// rows of 128 bytes (two to a period, already apart by half of it) with ((row >> 1) & 7).
-template <int RB>
-__device__ __forceinline__ int k_row_swizzle(int row) { return RB >= 256 ? (row & 15) : ((row >> 1) & 7); }
-
 template <int RB, int NW, int NLD, bool VSWZ = false>
 __device__ __forceinline__ void lds_fill_offsets(int w, int lane, int (&off)[NLD]) {
 #pragma unroll

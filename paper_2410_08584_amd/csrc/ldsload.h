@@ -4,9 +4,17 @@
 
 namespace zipvl {
 
-// byte offset of logical 16-byte chunk `c` in a swizzled LDS row (sw = row & 7): rows are unpadded, and the
-// XOR makes 8 consecutive rows read at the same logical chunk hit 8 different bank groups
+// byte offset of logical 16-byte chunk `c` in a swizzled LDS row (sw = the row's swizzle): rows are unpadded, and
+// the XOR makes consecutive rows read at the same logical chunk hit different bank groups
 __device__ __forceinline__ int swz_chunk(int c, int sw) { return (c ^ sw) << 4; }
+
+// Row swizzle of a tile whose rows are read 32 at a time at one logical chunk (key rows): the LDS
+// serves a 16-byte-per-lane read 16 lanes per clock from 64 banks (256 bytes), so 16 consecutive rows must
+// land on 16 different chunks of that period: rows of 256 bytes or more XOR the chunk index with (row & 15),
+// rows of 128 bytes (two to a period, already apart by half of it) with ((row >> 1) & 7).
+template <int RB>
+__device__ __forceinline__ int k_row_swizzle(int row) { return RB >= 256 ? (row & 15) : ((row >> 1) & 7); }
+
 
 __device__ __forceinline__ unsigned lds_address(const char* p) {
     return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) char*)p;

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
     for (int q = 0; q < NLD; ++q) {
         const int o = (q * NWV + w) * 1024 + lane * 16;              // LDS byte of the piece: row r, position p of the row
         const int r = o / RB, p = (o % RB) >> 4;
-        ld_off[q] = r * row_stride + ((p ^ (r & 7)) << 4);
+        ld_off[q] = r * row_stride + ((p ^ k_row_swizzle<RB>(r)) << 4);
     }
     // Every wave issues exactly NLD loads per stage (pieces past the chunk's or the sequence's last row re-read
     // the stage's first row and are never used), so that "all but the newest p stages have landed" is a count.
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(64 * NWV, (Elem<T>::kBytes == 4 && D == 128 && NWV 
                         continue;
                     }
                     const char* krow = kb0 + (kb * 32 + i) * RB;
-                    auto kfrag = [&](int cc) { return *reinterpret_cast<const uintx4*>(krow + swz_chunk(2 * cc + h, i & 7)); };
+                    auto kfrag = [&](int cc) { return *reinterpret_cast<const uintx4*>(krow + swz_chunk(2 * cc + h, k_row_swizzle<RB>(i))); };
                     floatx16 acc = {0};
                     const bool masked = has_pad || jb + 31 > Pmin;  // wave-uniform
                     if (PASS == 1) {
