@@ -343,18 +343,6 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     int kk = kcnt ? kcnt[t_per_batch ? b : u] : n;
     kk = max(0, min(kk, n));
     if (i0 >= kk) return;
-    // kept-token coordinates of this lane's QB queries, their positions, their Q fragments
-    int qrow[QB], qpos[QB];
-    uintx4 qf[QB][C::CH];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        qrow[qb] = i0 + kRW * w + 32 * qb + i;
-        const int qclamp = min(qrow[qb], kk - 1);
-        qpos[qb] = tidx ? tidx[qclamp] : qclamp;
-        const T* qp = Q + b * qs0 + head * qs1 + (int64_t)qpos[qb] * qs2;
-#pragma unroll
-        for (int cc = 0; cc < C::CH; ++cc) qf[qb][cc] = load16(qp + cc * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
-    }
     floatx16 o[QB][C::ODB];
     float m_run[QB], l_run[QB];
 
@@ -373,6 +361,26 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     PV<T, D, NW, QB>::lane_offsets(lane, vlane);
 
     const unsigned klds = lds_address(Kb0) + w * 1024, vlds = lds_address(Vb0) + w * 1024;
+    // The first tiles are requested before anything else is loaded: their addresses need only scalars, while the
+    // query rows below wait for their positions first (two round trips).
+    auto request_first_tiles = [&]() {
+        tile_to_lds<C::KRB, NW, C::NLD>(kg, Kb0, w, koff);
+        tile_to_lds<C::VRB, NW, C::NLD>(vg, Vb0, w, voff);
+        if (ntiles > 1) tile_to_lds<C::KRB, NW, C::NLD>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
+    };
+    request_first_tiles();
+    // kept-token coordinates of this lane's QB queries, their positions, their Q fragments
+    int qrow[QB], qpos[QB];
+    uintx4 qf[QB][C::CH];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qrow[qb] = i0 + kRW * w + 32 * qb + i;
+        const int qclamp = min(qrow[qb], kk - 1);
+        qpos[qb] = tidx ? tidx[qclamp] : qclamp;
+        const T* qp = Q + b * qs0 + head * qs1 + (int64_t)qpos[qb] * qs2;
+#pragma unroll
+        for (int cc = 0; cc < C::CH; ++cc) qf[qb][cc] = load16(qp + cc * Elem<T>::kPerChunk + h * Elem<T>::kPerFrag);
+    }
     // One pass over the key tiles.  SAFE = false: the exponent offset stays 0 (softmax is shift invariant, and
     // floating point keeps its relative precision at any magnitude), so there is no running maximum, no
     // exchange between lanes and no rescaling in the loop; valid as long as the row sums stay far inside the
@@ -394,9 +402,7 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     // second half of step t+1; V tile t+1 is requested in the second half of step t and first read at the
     // start of step t+2: every tile has a whole step to arrive.  Two barriers per step (middle and end),
     // each preceded by a wait that leaves this wave's two most recent tile requests outstanding.
-    tile_to_lds<C::KRB, NW, C::NLD>(kg, Kb0, w, koff);
-    tile_to_lds<C::VRB, NW, C::NLD>(vg, Vb0, w, voff);
-    if (ntiles > 1) tile_to_lds<C::KRB, NW, C::NLD>(kg + C::TILE_BYTES, Kb0 + C::TILE_BYTES, w, koff);
+    if constexpr (SAFE) request_first_tiles();                  // the first pass requested them before the query rows
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     floatx16 sa[QB][2], sb[QB][2];
@@ -642,6 +648,18 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
     __builtin_amdgcn_s_waitcnt(0);
     };
     pass(std::false_type{});
+    // Output rows.  Everything the stores need is derived again from the thread index here (the empty asm
+    // keeps the compiler from carrying row numbers and pointers through the key loop, where registers are
+    // scarce); the positions are requested now and arrive during the check below.
+    int tid_out = threadIdx.x;
+    asm volatile("" : "+v"(tid_out));
+    const int w_out = tid_out >> 6, i_out = tid_out & 31, h_out = (tid_out >> 5) & 1;
+    int qr_out[QB], orow_out[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qr_out[qb] = i0 + kRW * w_out + 32 * qb + i_out;
+        orow_out[qb] = (out_compact || !tidx) ? qr_out[qb] : tidx[min(qr_out[qb], kk - 1)];
+    }
     {
         // the offset-free pass stands if every row sum of the workgroup is finite and far from both ends of the
         // fp32 range (no exponential overflowed, the dominant terms did not underflow); otherwise the whole
@@ -655,18 +673,13 @@ __global__ __launch_bounds__(64 * NW, (AttnCfg<T, D, NW, QB>::MIN_WGS)) void fla
         if (__syncthreads_or(bad)) pass(std::true_type{});
     }
 
-    // Output rows.  Everything the stores need is derived again from the thread index here (the empty asm
-    // keeps the compiler from carrying row numbers and pointers through the key loop, where registers are scarce).
-    int tid_out = threadIdx.x;
-    asm volatile("" : "+v"(tid_out));
-    const int w_out = tid_out >> 6, i_out = tid_out & 31, h_out = (tid_out >> 5) & 1;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float l_tot = xhalf_sum(l_run[qb]);
-        const int qr = i0 + kRW * w_out + 32 * qb + i_out;
+        const int qr = qr_out[qb];
         if (qr < kk) {
             const float inv = 1.f / l_tot;
-            const int orow = (out_compact || !tidx) ? qr : tidx[qr];
+            const int orow = orow_out[qb];
             T* op = O + ((int64_t)bh * n + orow) * D;
 #pragma unroll
             for (int db = 0; db < C::ODB; ++db)
