@@ -178,6 +178,10 @@ int zipvl_share_scores(const float* mass, const float* rank, int B, int Hkv, int
  * (with ZIPVL_T_PER_BATCH, T of unit u is idx[b, 0..k[b]-1]).
  * O [device] [B,Hq,n,d] contiguous, dtype as the inputs.
  * ws [device] zipvl_workspace_bytes(ZIPVL_OP_SPARSE_PREFILL, dims, 0) bytes, 256-byte aligned.
+ * Numerics: accumulation in fp32; probabilities of a bf16 call are rounded to bf16 before they weigh V and before
+ * they are summed.  Logits of any finite magnitude are handled: rows whose scaled logits all lie within about
+ * +-44 of zero are exponentiated without an offset, a workgroup with any other row repeats its keys with running
+ * maxima (twice the time for that workgroup, the same result up to rounding).  Inputs must be finite.
  */
 int zipvl_sparse_prefill(const void* Q, const void* K, const void* V, const zipvl_dims* dims,
                          const int32_t* idx, const int32_t* k, float softmax_scale, int flags,
