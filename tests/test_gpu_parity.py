@@ -335,12 +335,15 @@ def test_attention_compact_output_rows():
     _attention_case(1, 4, 2, 500, 128, "bf16", [333, 128], seed=7, flags=z.OUT_COMPACT)
 
 
-@pytest.mark.parametrize("n", [400, 448])
-def test_attention_on_already_compacted_cache(n):
-    # n = 448 (whole 64-row tiles, contiguous rows) reads the evicted K cache in place; n = 400 repacks it
-    say(f"attention KV_ALREADY_COMPACT n={n}")
+@pytest.mark.parametrize("n,gain", [(400, 1.0), (448, 1.0), (448, 40.0)])
+def test_attention_on_already_compacted_cache(n, gain):
+    # n = 448 (whole 64-row tiles, contiguous rows) reads the evicted K cache in place; n = 400 repacks it;
+    # gain 40: logits far outside the range the offset-free pass accepts, so every workgroup repeats its keys
+    say(f"attention KV_ALREADY_COMPACT n={n} gain={gain}")
     B, Hq, Hkv, d, dtype = 1, 4, 2, 128, "bf16"
     w = make_custom(B, Hq, Hkv, n, d, dtype, seed=8)
+    if gain != 1.0:
+        w.Q = torch.from_numpy(w.Q * np.float32(gain)).bfloat16().float().numpy()
     Q, K, V = dev(w.Q, dtype), dev(w.K, dtype), dev(w.V, dtype)
     ks = [211, 77]
     r = np.random.Generator(np.random.PCG64(9))
@@ -357,6 +360,11 @@ def test_attention_on_already_compacted_cache(n):
     torch.cuda.synchronize()
     assert not torch.isnan(O2.float()).any()
     assert torch.equal(O1, O2)
+    Oh, G = host64(O2), Hq // Hkv
+    worst = max(np.abs(Oh[0, h] - oz.kept_token_attention(w.Q[0, h], w.K[0, h // G], w.V[0, h // G], idx[h // G, :ks[h // G]], w.scale)).max()
+                for h in range(Hq))
+    say(f"  worst |dO| = {worst:.3e}")
+    assert worst <= ATOL_OUT[dtype]
 
 
 # ------------------------------------------------------------------ whole layer
