@@ -496,6 +496,9 @@ def main():
             step()                                           # eager work between the replays
             torch.cuda.synchronize()
         if ok:
+            for _ in range(args.warmup):                     # the checks above left gaps: warm-up replays, then the timed ones
+                g.replay()
+            torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(args.steps):
                 g.replay()
